@@ -1,0 +1,174 @@
+/*
+ * emoe.h -- C ABI of the resident-expert MoE layer for AMD MI355X (gfx950).
+ *
+ * One MoE layer forward ("a gate and a collection of experts", eMoE Section 1)
+ * computed over only those experts that are currently resident in GPU memory.
+ * The rule that makes this the paper's layer and not the ordinary one is in
+ * Section 3.2.2 (last paragraph): a token whose chosen expert is not on the
+ * GPU is routed to its next-best expert that is.
+ *
+ * Notation: T tokens, d = d_model, f = d_ff, E experts, k experts per token,
+ * S expert slots in GPU memory (a slot holds one expert's weights or is
+ * empty), A = T*k assignments; assignment a = t*k + j is token t's j-th choice.
+ *
+ * Conventions for every entry point
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses; the caller owns every buffer; the library allocates nothing,
+ *     frees nothing and keeps no state between calls.
+ *   - Tensors are dense row-major.  Element type is desc->dtype: fp32, or
+ *     bf16 stored as 16-bit patterns.  Pointers must be 16-byte aligned.
+ *   - `stream` is a hipStream_t (NULL = the null stream).  Calls only enqueue
+ *     work on it; none synchronises with the host.
+ *   - Return value: EMOE_OK or a negative emoe_status.  Arguments are checked
+ *     on the host before anything is enqueued; on a validation error nothing
+ *     is enqueued and no output is touched.  T == 0 is a successful no-op.
+ *   - Limits: 1 <= k <= S <= E <= 64; d_model and d_ff multiples of 8;
+ *     T*k < 2^31 / max(d_model, d_ff).
+ */
+#ifndef EMOE_H
+#define EMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EMOE_OK = 0,
+    EMOE_ERR_NULL = -1,        /* a required pointer is NULL */
+    EMOE_ERR_SHAPE = -2,       /* an extent is out of range or inconsistent */
+    EMOE_ERR_UNSUPPORTED = -3, /* unknown dtype / activation, E > 64, extent not a multiple of 8 */
+    EMOE_ERR_RESIDENT = -4,    /* bad expert or slot id, duplicate slot, fewer than k resident experts */
+    EMOE_ERR_WORKSPACE = -5,   /* workspace pointer NULL or too small */
+    EMOE_ERR_DEVICE = -6       /* a HIP runtime call failed */
+} emoe_status;
+
+typedef enum { EMOE_F32 = 0, EMOE_BF16 = 1 } emoe_dtype;
+typedef enum { EMOE_ACT_SWIGLU = 0, EMOE_ACT_RELU = 1 } emoe_act;
+
+typedef struct {
+    int32_t T;       /* tokens in this call                         */
+    int32_t d_model; /* d                                           */
+    int32_t d_ff;    /* f                                           */
+    int32_t E;       /* experts the gate scores                     */
+    int32_t k;       /* experts per token                           */
+    int32_t S;       /* expert slots in GPU memory                  */
+    int32_t dtype;   /* emoe_dtype of x, weights, x_perm, y_perm, out */
+    int32_t act;     /* emoe_act                                    */
+} emoe_layer_desc;
+
+/* Static description of a status code; never NULL, never freed. */
+const char *emoe_status_string(int status);
+
+/* Bytes of device workspace emoe_permute and emoe_expert_ffn need for `desc`
+ * (either output pointer may be NULL).  Pure host arithmetic. */
+int emoe_workspace_bytes(const emoe_layer_desc *desc, size_t *permute_ws_bytes, size_t *ffn_ws_bytes);
+
+/*
+ * Gate and resident-restricted top-k (Section 1: the gate; Section 3.2.2: fallback
+ * to the next-best resident expert; Section 3.2.2 first paragraphs: the routing
+ * result is "a series of k indices" per token).
+ *   logit[t,e] = sum_i x[t,i] * w_gate[e,i] (+ gate_bias[e]), fp32 accumulation.
+ *   Among experts with slot_of_expert[e] >= 0, the k largest logits in descending
+ *   order (ties: lower expert index) -> topk_expert[t,0..k-1] (expert ids).
+ *   topk_weight[t,j] = softmax over those k logits (fp32; sums to 1).
+ * x [T,d] dev, w_gate [E,d] dev, gate_bias [E] fp32 dev or NULL,
+ * slot_of_expert [E] int32 dev (-1 = not resident),
+ * topk_expert [T,k] int32 dev (out), topk_weight [T,k] fp32 dev (out).
+ * Precondition (not checkable on the host): at least k experts are resident;
+ * emoe_load_experts never produces a map that violates it.  If it is violated
+ * the outputs are unspecified, but every later call still stays in bounds.
+ */
+int emoe_route(const emoe_layer_desc *desc, const void *x, const void *w_gate, const float *gate_bias,
+               const int32_t *slot_of_expert, int32_t *topk_expert, float *topk_weight, void *stream);
+
+/*
+ * Token permutation into per-slot groups (the per-expert token count is the
+ * "workload" of Section 3.2.2).  Stable counting sort of the assignments
+ * a = 0..A-1 by key slot_of_expert[topk_expert[a]]:
+ *   slot_counts[s]  = number of assignments in slot s (0 for empty slots),
+ *   slot_offsets    = exclusive prefix sum of slot_counts, length S+1,
+ *   perm[r] = a     : row r of the grouped order holds assignment a,
+ *   inv_perm[a] = r,
+ *   x_perm[r,:]     = x[perm[r] / k, :]   (bit copy).
+ * All outputs dev; ws dev, ws_bytes >= permute_ws_bytes of emoe_workspace_bytes.
+ */
+int emoe_permute(const emoe_layer_desc *desc, const void *x, const int32_t *topk_expert,
+                 const int32_t *slot_of_expert, int32_t *slot_counts, int32_t *slot_offsets, int32_t *perm,
+                 int32_t *inv_perm, void *x_perm, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Expert FFN over the grouped rows, only for slots that received rows ("fewer
+ * experts ... reduce the compute latency and global GPU memory read operations",
+ * Section 5.1).  For slot s and rows r in [slot_offsets[s], slot_offsets[s+1]):
+ *   SwiGLU: h = silu(x_perm[r] W1_s^T) * (x_perm[r] W3_s^T),  y_perm[r] = h W2_s^T
+ *   ReLU  : h = max(x_perm[r] W1_s^T, 0),                      y_perm[r] = h W2_s^T
+ * Products accumulate in fp32; h and y_perm are rounded once to dtype.
+ * x_perm [A,d] dev; slot_offsets [S+1] dev; w1_slots, w3_slots [S,f,d] dev
+ * (w3_slots must be NULL for ReLU and non-NULL for SwiGLU); w2_slots [S,d,f] dev;
+ * y_perm [A,d] dev (out); ws dev, ws_bytes >= ffn_ws_bytes.
+ */
+int emoe_expert_ffn(const emoe_layer_desc *desc, const void *x_perm, const int32_t *slot_offsets,
+                    const void *w1_slots, const void *w3_slots, const void *w2_slots, void *y_perm, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/*
+ * One half of emoe_expert_ffn, with the same arguments and checks: pass 1 computes
+ * h (into ws) from x_perm, pass 2 computes y_perm from the h that pass 1 left in ws.
+ * Calling pass 1 then pass 2 on one stream is emoe_expert_ffn.  Exists so that each of the two
+ * grouped products can be timed and profiled on its own.  Any other `pass`: EMOE_ERR_SHAPE.
+ */
+int emoe_expert_ffn_pass(const emoe_layer_desc *desc, int32_t pass, const void *x_perm,
+                         const int32_t *slot_offsets, const void *w1_slots, const void *w3_slots,
+                         const void *w2_slots, void *y_perm, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Gate-weighted combine back to token order (Section 1):
+ *   out[t,:] = sum_{j<k} topk_weight[t,j] * y_perm[inv_perm[t*k+j], :], j ascending,
+ * fp32 accumulation, one rounding to dtype.  out [T,d] dev.
+ */
+int emoe_combine(const emoe_layer_desc *desc, const void *y_perm, const int32_t *inv_perm,
+                 const float *topk_weight, void *out, void *stream);
+
+/*
+ * Change the resident set (Section 3.2.2: predicted experts not yet on the GPU are
+ * loaded, the others leave; Section 4: loads are asynchronous host-to-device copies,
+ * the layer waits on an event recorded after its load so it never sees stale
+ * weights, and loads are issued one after the other so the host link is not
+ * oversubscribed).
+ *
+ * For i in 0..n-1 (in this order): slot slot_ids[i] receives expert expert_ids[i];
+ * expert_ids[i] == -1 only empties the slot.  An expert already resident in
+ * another slot moves (its old slot becomes empty).  Whatever the slot held before
+ * is dropped; the host keeps the master copy of every expert, nothing is copied back.
+ *
+ * host_w1/w3/w2: host arrays of E host pointers to each expert's weights in
+ * canonical layout W1 [f,d], W3 [f,d], W2 [d,f]; only entries named in expert_ids
+ * are read; they must stay valid and unchanged until done_event (or the stream)
+ * completes, and should be pinned for the copy to be asynchronous.  host_w3 may
+ * be NULL for ReLU.
+ * w1_slots/w3_slots/w2_slots: dev slot buffers [S,f,d], [S,f,d], [S,d,f].
+ * slot_of_expert [E] dev, expert_of_slot [S] dev: the device maps (out).
+ * expert_of_slot_host [S] host (in/out): the caller's mirror of expert_of_slot
+ * (-1 = empty); read to validate the change, updated on success.
+ *
+ * Order on side_stream: wait wait_event (if not NULL: "no layer forward still
+ * reads these slots") -> copies in list order -> both device maps rewritten ->
+ * record done_event (if not NULL).  A forward that must see the new experts
+ * waits on done_event first.
+ * Errors (nothing enqueued, mirror untouched): EMOE_ERR_RESIDENT for ids out of
+ * range, a slot named twice, an expert named twice, or a resulting map with fewer
+ * than k resident experts.
+ */
+int emoe_load_experts(const emoe_layer_desc *desc, int32_t n, const int32_t *expert_ids, const int32_t *slot_ids,
+                      const void *const *host_w1, const void *const *host_w3, const void *const *host_w2,
+                      void *w1_slots, void *w3_slots, void *w2_slots, int32_t *slot_of_expert,
+                      int32_t *expert_of_slot, int32_t *expert_of_slot_host, void *side_stream, void *wait_event,
+                      void *done_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMOE_H */

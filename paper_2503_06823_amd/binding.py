@@ -1,0 +1,182 @@
+"""ctypes binding of libemoe.so: argument marshalling only.
+
+Every step of the layer runs in the HIP kernels behind the C ABI declared in include/emoe.h.
+Tensor arguments are torch tensors (device memory comes from torch; `.data_ptr()` is what crosses
+the boundary) or plain integer addresses.  There is no fallback: if the library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libemoe.so")
+
+EMOE_OK = 0
+EMOE_ERR_NULL, EMOE_ERR_SHAPE, EMOE_ERR_UNSUPPORTED = -1, -2, -3
+EMOE_ERR_RESIDENT, EMOE_ERR_WORKSPACE, EMOE_ERR_DEVICE = -4, -5, -6
+EMOE_F32, EMOE_BF16 = 0, 1
+EMOE_ACT_SWIGLU, EMOE_ACT_RELU = 0, 1
+DTYPES = {"f32": EMOE_F32, "bf16": EMOE_BF16}
+ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
+
+EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_permute", "emoe_expert_ffn",
+           "emoe_expert_ffn_pass", "emoe_combine", "emoe_load_experts")
+
+
+class EmoeLayerDesc(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("act", ctypes.c_int32)]
+
+
+class EmoeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (see build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2503_06823_amd.build` "
+                                    "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        dp = ctypes.POINTER(EmoeLayerDesc)
+        L.emoe_status_string.restype = ctypes.c_char_p
+        L.emoe_status_string.argtypes = [ctypes.c_int]
+        L.emoe_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.emoe_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+        L.emoe_permute.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.emoe_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.emoe_expert_ffn_pass.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.emoe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.emoe_load_experts.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        for name in EXPORTS[1:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().emoe_status_string(int(status)).decode()
+
+
+def make_desc(T: int, d_model: int, d_ff: int, E: int, k: int, S: int, dtype, act) -> EmoeLayerDesc:
+    return EmoeLayerDesc(T, d_model, d_ff, E, k, S, DTYPES.get(dtype, dtype), ACTS.get(act, act))
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    """Address of a torch tensor / numpy array / raw int / None."""
+    if t is None:
+        return ctypes.c_void_p(0)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if hasattr(t, "data_ptr"):
+        return ctypes.c_void_p(t.data_ptr())
+    if hasattr(t, "ctypes"):
+        return ctypes.c_void_p(t.ctypes.data)
+    raise TypeError(f"cannot take the address of {type(t)}")
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _event(ev) -> ctypes.c_void_p:
+    if ev is None:
+        return ctypes.c_void_p(0)
+    if isinstance(ev, int):
+        return ctypes.c_void_p(ev)
+    return ctypes.c_void_p(ev.cuda_event)
+
+
+def _check(rc: int, where: str, check: bool) -> int:
+    if check and rc != EMOE_OK:
+        raise EmoeError(rc, where)
+    return rc
+
+
+def emoe_workspace_bytes(desc: EmoeLayerDesc, check: bool = True) -> Tuple[int, int]:
+    a, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    rc = lib().emoe_workspace_bytes(ctypes.byref(desc), ctypes.byref(a), ctypes.byref(b))
+    _check(rc, "emoe_workspace_bytes", check)
+    return (a.value, b.value) if rc == EMOE_OK else (rc, rc)
+
+
+def emoe_route(desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_weight, stream=None, check=True) -> int:
+    rc = lib().emoe_route(ctypes.byref(desc), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(slot_of_expert),
+                          _ptr(topk_expert), _ptr(topk_weight), _stream(stream))
+    return _check(rc, "emoe_route", check)
+
+
+def emoe_permute(desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm, x_perm, ws,
+                 ws_bytes, stream=None, check=True) -> int:
+    rc = lib().emoe_permute(ctypes.byref(desc), _ptr(x), _ptr(topk_expert), _ptr(slot_of_expert), _ptr(slot_counts),
+                            _ptr(slot_offsets), _ptr(perm), _ptr(inv_perm), _ptr(x_perm), _ptr(ws), int(ws_bytes),
+                            _stream(stream))
+    return _check(rc, "emoe_permute", check)
+
+
+def emoe_expert_ffn(desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes, stream=None,
+                    check=True) -> int:
+    rc = lib().emoe_expert_ffn(ctypes.byref(desc), _ptr(x_perm), _ptr(slot_offsets), _ptr(w1_slots), _ptr(w3_slots),
+                               _ptr(w2_slots), _ptr(y_perm), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(rc, "emoe_expert_ffn", check)
+
+
+def emoe_expert_ffn_pass(desc, which, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+                         stream=None, check=True) -> int:
+    rc = lib().emoe_expert_ffn_pass(ctypes.byref(desc), int(which), _ptr(x_perm), _ptr(slot_offsets), _ptr(w1_slots),
+                                    _ptr(w3_slots), _ptr(w2_slots), _ptr(y_perm), _ptr(ws), int(ws_bytes),
+                                    _stream(stream))
+    return _check(rc, "emoe_expert_ffn_pass", check)
+
+
+def emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream=None, check=True) -> int:
+    rc = lib().emoe_combine(ctypes.byref(desc), _ptr(y_perm), _ptr(inv_perm), _ptr(topk_weight), _ptr(out),
+                            _stream(stream))
+    return _check(rc, "emoe_combine", check)
+
+
+def _i32_array(values: Optional[Sequence[int]]):
+    if values is None:
+        return None
+    return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+
+
+def _ptr_array(tensors: Optional[Sequence], E: int):
+    """Host array of E host pointers (NULL where the caller gave None)."""
+    if tensors is None:
+        return None
+    assert len(tensors) == E, "one entry (tensor or None) per expert"
+    return (ctypes.c_void_p * E)(*[_ptr(t) for t in tensors])
+
+
+def emoe_load_experts(desc, expert_ids, slot_ids, host_w1, host_w3, host_w2, w1_slots, w3_slots, w2_slots,
+                      slot_of_expert, expert_of_slot, expert_of_slot_host, side_stream, wait_event=None,
+                      done_event=None, check=True) -> int:
+    """`host_w*`: sequences of E pinned host tensors (or None entries); `expert_of_slot_host`: a
+    contiguous int32 numpy array or CPU tensor of length S, updated in place on success."""
+    n = 0 if expert_ids is None else len(expert_ids)
+    ids, slots = _i32_array(expert_ids), _i32_array(slot_ids)
+    a1, a3, a2 = _ptr_array(host_w1, desc.E), _ptr_array(host_w3, desc.E), _ptr_array(host_w2, desc.E)
+    cast = lambda a: ctypes.cast(a, ctypes.c_void_p) if a is not None else ctypes.c_void_p(0)
+    rc = lib().emoe_load_experts(ctypes.byref(desc), n, cast(ids), cast(slots), cast(a1), cast(a3), cast(a2),
+                                 _ptr(w1_slots), _ptr(w3_slots), _ptr(w2_slots), _ptr(slot_of_expert),
+                                 _ptr(expert_of_slot), _ptr(expert_of_slot_host), _stream(side_stream),
+                                 _event(wait_event), _event(done_event))
+    return _check(rc, "emoe_load_experts", check)

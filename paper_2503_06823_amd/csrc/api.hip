@@ -1,0 +1,229 @@
+// C ABI of libemoe: host-side argument checks, workspace layout, dispatch to the kernels.
+// The operations are documented in include/emoe.h.
+#include <string.h>
+
+#include "common.h"
+
+namespace emoe {
+
+namespace {
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+size_t elem_bytes(const emoe_layer_desc& d) { return d.dtype == EMOE_F32 ? 4 : 2; }
+}  // namespace
+
+int validate_desc(const emoe_layer_desc* d) {
+    if (d == nullptr) return EMOE_ERR_NULL;
+    if (d->dtype != EMOE_F32 && d->dtype != EMOE_BF16) return EMOE_ERR_UNSUPPORTED;
+    if (d->act != EMOE_ACT_SWIGLU && d->act != EMOE_ACT_RELU) return EMOE_ERR_UNSUPPORTED;
+    if (d->T < 0 || d->d_model <= 0 || d->d_ff <= 0 || d->E <= 0 || d->k <= 0 || d->S <= 0) return EMOE_ERR_SHAPE;
+    if (d->k > d->S || d->S > d->E) return EMOE_ERR_SHAPE;
+    if (d->E > kMaxExperts) return EMOE_ERR_UNSUPPORTED;
+    if (d->d_model % 8 != 0 || d->d_ff % 8 != 0) return EMOE_ERR_UNSUPPORTED;
+    const long long A = (long long)d->T * d->k;
+    const long long widest = d->d_model > d->d_ff ? d->d_model : d->d_ff;
+    if (A * widest >= (1ll << 31)) return EMOE_ERR_SHAPE;
+    return EMOE_OK;
+}
+
+PermuteWs permute_ws_layout(const emoe_layer_desc& d) {
+    PermuteWs w;
+    const long long A = (long long)d.T * d.k;
+    const long long n_blocks = (A + kPermuteChunk - 1) / kPermuteChunk;
+    w.block_counts = 0;
+    w.total = align256((size_t)(n_blocks > 0 ? n_blocks : 1) * d.S * sizeof(int32_t));
+    return w;
+}
+
+FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
+    FfnWs w;
+    const size_t A = (size_t)d.T * d.k;
+    w.h = 0;
+    w.total = align256((A > 0 ? A : 1) * d.d_ff * elem_bytes(d));
+    return w;
+}
+
+// Few rows per slot: reading the weights dominates, use the streaming kernels.  The tiled
+// kernels pad every non-empty slot to 256 rows, the streaming ones to 32 (and re-read the
+// weights once per further 64 rows), so the switch sits where both cost about the same.
+bool ffn_use_stream_path(const emoe_layer_desc& d) {
+    const long long A = (long long)d.T * d.k;
+    return A <= 48ll * d.S;
+}
+
+}  // namespace emoe
+
+using namespace emoe;
+
+extern "C" {
+
+const char* emoe_status_string(int status) {
+    switch (status) {
+        case EMOE_OK: return "ok";
+        case EMOE_ERR_NULL: return "a required pointer is NULL";
+        case EMOE_ERR_SHAPE: return "an extent is out of range or inconsistent";
+        case EMOE_ERR_UNSUPPORTED: return "unsupported dtype, activation or extent";
+        case EMOE_ERR_RESIDENT: return "bad expert or slot id, duplicate, or fewer than k resident experts";
+        case EMOE_ERR_WORKSPACE: return "workspace missing or too small";
+        case EMOE_ERR_DEVICE: return "a HIP runtime call failed";
+        default: return "unknown status";
+    }
+}
+
+int emoe_workspace_bytes(const emoe_layer_desc* desc, size_t* permute_ws_bytes, size_t* ffn_ws_bytes) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (permute_ws_bytes) *permute_ws_bytes = permute_ws_layout(*desc).total;
+    if (ffn_ws_bytes) *ffn_ws_bytes = ffn_ws_layout(*desc).total;
+    return EMOE_OK;
+}
+
+int emoe_route(const emoe_layer_desc* desc, const void* x, const void* w_gate, const float* gate_bias,
+               const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, void* stream) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!x || !w_gate || !slot_of_expert || !topk_expert || !topk_weight) return EMOE_ERR_NULL;
+    if (desc->T == 0) return EMOE_OK;
+    hipError_t e = launch_route(*desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_weight,
+                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}
+
+int emoe_permute(const emoe_layer_desc* desc, const void* x, const int32_t* topk_expert,
+                 const int32_t* slot_of_expert, int32_t* slot_counts, int32_t* slot_offsets, int32_t* perm,
+                 int32_t* inv_perm, void* x_perm, void* ws, size_t ws_bytes, void* stream) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!x || !topk_expert || !slot_of_expert || !slot_counts || !slot_offsets || !perm || !inv_perm || !x_perm)
+        return EMOE_ERR_NULL;
+    if (!ws || ws_bytes < permute_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (desc->T == 0) {  // no assignments: every slot is empty
+        hipError_t z1 = launch_fill_i32(slot_counts, desc->S, 0, st);
+        hipError_t z2 = launch_fill_i32(slot_offsets, desc->S + 1, 0, st);
+        return (z1 == hipSuccess && z2 == hipSuccess) ? EMOE_OK : EMOE_ERR_DEVICE;
+    }
+    hipError_t e = launch_permute(*desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm,
+                                  x_perm, ws, st);
+    return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}
+
+static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void* x_perm,
+                             const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
+                             const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!x_perm || !slot_offsets || !w1_slots || !w2_slots || !y_perm) return EMOE_ERR_NULL;
+    if (desc->act == EMOE_ACT_SWIGLU && !w3_slots) return EMOE_ERR_NULL;
+    if (desc->act == EMOE_ACT_RELU && w3_slots) return EMOE_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < ffn_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
+    if (desc->T == 0) return EMOE_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (desc->dtype == EMOE_F32)
+        e = launch_ffn_f32(*desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+    else if (ffn_use_stream_path(*desc))
+        e = launch_ffn_bf16_stream(*desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+    else
+        e = launch_ffn_bf16_tiled(*desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+    return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}
+
+int emoe_expert_ffn(const emoe_layer_desc* desc, const void* x_perm, const int32_t* slot_offsets,
+                    const void* w1_slots, const void* w3_slots, const void* w2_slots, void* y_perm, void* ws,
+                    size_t ws_bytes, void* stream) {
+    return expert_ffn_passes(desc, 3, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+                             stream);
+}
+
+int emoe_expert_ffn_pass(const emoe_layer_desc* desc, int32_t pass, const void* x_perm, const int32_t* slot_offsets,
+                         const void* w1_slots, const void* w3_slots, const void* w2_slots, void* y_perm, void* ws,
+                         size_t ws_bytes, void* stream) {
+    if (pass != 1 && pass != 2) return EMOE_ERR_SHAPE;
+    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws,
+                             ws_bytes, stream);
+}
+
+int emoe_combine(const emoe_layer_desc* desc, const void* y_perm, const int32_t* inv_perm, const float* topk_weight,
+                 void* out, void* stream) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!y_perm || !inv_perm || !topk_weight || !out) return EMOE_ERR_NULL;
+    if (desc->T == 0) return EMOE_OK;
+    hipError_t e = launch_combine(*desc, y_perm, inv_perm, topk_weight, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}
+
+int emoe_load_experts(const emoe_layer_desc* desc, int32_t n, const int32_t* expert_ids, const int32_t* slot_ids,
+                      const void* const* host_w1, const void* const* host_w3, const void* const* host_w2,
+                      void* w1_slots, void* w3_slots, void* w2_slots, int32_t* slot_of_expert,
+                      int32_t* expert_of_slot, int32_t* expert_of_slot_host, void* side_stream, void* wait_event,
+                      void* done_event) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (n < 0 || n > desc->S) return EMOE_ERR_SHAPE;
+    if (!slot_of_expert || !expert_of_slot || !expert_of_slot_host || !w1_slots || !w2_slots) return EMOE_ERR_NULL;
+    if (n > 0 && (!expert_ids || !slot_ids || !host_w1 || !host_w2)) return EMOE_ERR_NULL;
+    const bool swiglu = desc->act == EMOE_ACT_SWIGLU;
+    if (swiglu && (!w3_slots || (n > 0 && !host_w3))) return EMOE_ERR_NULL;
+    const int E = desc->E, S = desc->S;
+
+    // ---- validate the change against the caller's mirror, on a copy -------------------------
+    int32_t eos[kMaxExperts], soe[kMaxExperts];
+    bool slot_named[kMaxExperts] = {}, expert_named[kMaxExperts] = {};
+    for (int s = 0; s < S; ++s) {
+        eos[s] = expert_of_slot_host[s];
+        if (eos[s] < -1 || eos[s] >= E) return EMOE_ERR_RESIDENT;
+    }
+    for (int i = 0; i < n; ++i) {
+        const int e = expert_ids[i], s = slot_ids[i];
+        if (s < 0 || s >= S || e < -1 || e >= E) return EMOE_ERR_RESIDENT;
+        if (slot_named[s]) return EMOE_ERR_RESIDENT;
+        slot_named[s] = true;
+        if (e >= 0) {
+            if (expert_named[e]) return EMOE_ERR_RESIDENT;
+            expert_named[e] = true;
+            if (!host_w1[e] || !host_w2[e] || (swiglu && !host_w3[e])) return EMOE_ERR_NULL;
+        }
+    }
+    for (int i = 0; i < n; ++i) {
+        const int e = expert_ids[i], s = slot_ids[i];
+        if (e >= 0)
+            for (int s2 = 0; s2 < S; ++s2)
+                if (eos[s2] == e) eos[s2] = -1;  // the expert moves: its old slot empties
+        eos[s] = e;
+    }
+    int resident = 0;
+    for (int e = 0; e < E; ++e) soe[e] = -1;
+    for (int s = 0; s < S; ++s)
+        if (eos[s] >= 0) {
+            if (soe[eos[s]] >= 0) return EMOE_ERR_RESIDENT;  // mirror held an expert twice
+            soe[eos[s]] = s;
+            ++resident;
+        }
+    if (resident < desc->k) return EMOE_ERR_RESIDENT;
+
+    // ---- enqueue: wait, copies in list order, maps, event -------------------------------------
+    hipStream_t st = static_cast<hipStream_t>(side_stream);
+    if (wait_event && hipStreamWaitEvent(st, static_cast<hipEvent_t>(wait_event), 0) != hipSuccess)
+        return EMOE_ERR_DEVICE;
+    const size_t mat_bytes = (size_t)desc->d_model * desc->d_ff * elem_bytes(*desc);
+    for (int i = 0; i < n; ++i) {
+        const int e = expert_ids[i], s = slot_ids[i];
+        if (e < 0) continue;
+        uint8_t* d1 = static_cast<uint8_t*>(w1_slots) + (size_t)s * mat_bytes;
+        uint8_t* d2 = static_cast<uint8_t*>(w2_slots) + (size_t)s * mat_bytes;
+        if (hipMemcpyAsync(d1, host_w1[e], mat_bytes, hipMemcpyHostToDevice, st) != hipSuccess) return EMOE_ERR_DEVICE;
+        if (swiglu) {
+            uint8_t* d3 = static_cast<uint8_t*>(w3_slots) + (size_t)s * mat_bytes;
+            if (hipMemcpyAsync(d3, host_w3[e], mat_bytes, hipMemcpyHostToDevice, st) != hipSuccess)
+                return EMOE_ERR_DEVICE;
+        }
+        if (hipMemcpyAsync(d2, host_w2[e], mat_bytes, hipMemcpyHostToDevice, st) != hipSuccess) return EMOE_ERR_DEVICE;
+    }
+    if (launch_write_maps(soe, E, eos, S, slot_of_expert, expert_of_slot, st) != hipSuccess) return EMOE_ERR_DEVICE;
+    if (done_event && hipEventRecord(static_cast<hipEvent_t>(done_event), st) != hipSuccess) return EMOE_ERR_DEVICE;
+    memcpy(expert_of_slot_host, eos, sizeof(int32_t) * S);
+    return EMOE_OK;
+}
+
+}  // extern "C"

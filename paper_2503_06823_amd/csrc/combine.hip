@@ -1,0 +1,92 @@
+// Gate-weighted combine back to token order (eMoE Section 1: the layer output mixes the chosen
+// experts' outputs with the gate's weights):
+//   out[t,:] = sum_{j<k} topk_weight[t,j] * y_perm[inv_perm[t*k+j], :]   (j ascending, fp32, one rounding)
+// One wavefront handles one (token, 16-byte-per-lane column chunk) unit; every load is a contiguous
+// 1 KiB piece of a y_perm row.  An assignment with inv_perm < 0 (left out by the permutation)
+// contributes nothing.
+#include "common.h"
+
+namespace emoe {
+namespace {
+
+template <typename T> struct Pack;
+template <> struct Pack<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static void load(const bf16_t* p, float (&v)[8]) {
+        uint4 r = *reinterpret_cast<const uint4*>(p);
+        uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static void store(bf16_t* p, const float (&v)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <> struct Pack<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const float* p, float (&v)[4]) {
+        float4 r = *reinterpret_cast<const float4*>(p);
+        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+    }
+    __device__ static void store(float* p, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_perm, const int32_t* __restrict__ inv_perm,
+                                                      const float* __restrict__ topk_weight, T* __restrict__ out,
+                                                      int T_, int d, int k, int chunks) {
+    constexpr int N = Pack<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const long long n_waves = ((long long)gridDim.x * blockDim.x) >> 6;
+    const long long units = (long long)T_ * chunks;
+    for (long long u = wave; u < units; u += n_waves) {
+        const int t = (int)(u / chunks);
+        const int c = (int)(u % chunks) * 64 * N + lane * N;
+        if (c >= d) continue;
+        float acc[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            const int r = inv_perm[(size_t)t * k + j];
+            if (r < 0) continue;
+            const float w = topk_weight[(size_t)t * k + j];
+            float v[N];
+            Pack<T>::load(y_perm + (size_t)r * d + c, v);
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+        }
+        Pack<T>::store(out + (size_t)t * d + c, acc);
+    }
+}
+
+template <typename T>
+hipError_t launch_t(const emoe_layer_desc& d, const void* y_perm, const int32_t* inv_perm, const float* w, void* out,
+                    hipStream_t st) {
+    constexpr int N = Pack<T>::N;
+    const int chunks = (d.d_model + 64 * N - 1) / (64 * N);
+    long long units = (long long)d.T * chunks;
+    long long blocks = (units + 3) / 4;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    combine_kernel<T><<<(int)blocks, 256, 0, st>>>(static_cast<const T*>(y_perm), inv_perm, w, static_cast<T*>(out),
+                                                   d.T, d.d_model, d.k, chunks);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_combine(const emoe_layer_desc& d, const void* y_perm, const int32_t* inv_perm,
+                          const float* topk_weight, void* out, hipStream_t st) {
+    if (d.dtype == EMOE_F32) return launch_t<float>(d, y_perm, inv_perm, topk_weight, out, st);
+    return launch_t<bf16_t>(d, y_perm, inv_perm, topk_weight, out, st);
+}
+
+}  // namespace emoe

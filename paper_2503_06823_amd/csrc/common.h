@@ -1,0 +1,71 @@
+// Internal declarations shared by the HIP sources of libemoe (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "emoe.h"
+
+namespace emoe {
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 64;
+
+typedef uint16_t bf16_t;  // storage pattern of a bfloat16
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f32(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_f32(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void store_from_f32(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_from_f32(bf16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// Workspace layout (all offsets multiples of 256 bytes).
+struct PermuteWs {
+    size_t block_counts;  // int32 [n_blocks][S]
+    size_t total;
+};
+struct FfnWs {
+    size_t h;  // dtype [A][f]
+    size_t total;
+};
+constexpr int kPermuteChunk = 1024;  // assignments per workgroup in the counting sort
+PermuteWs permute_ws_layout(const emoe_layer_desc& d);
+FfnWs ffn_ws_layout(const emoe_layer_desc& d);
+
+// True when the FFN runs the weight-streaming (small batch) kernels instead of the tiled GEMM.
+bool ffn_use_stream_path(const emoe_layer_desc& d);
+
+// Host-side checks common to the entry points; returns EMOE_OK or an error.
+int validate_desc(const emoe_layer_desc* d);
+
+// `passes` of the FFN launchers: bit 0 = pass 1 (x_perm -> h), bit 1 = pass 2 (h -> y_perm).
+// Kernel launchers (each returns a hipError_t converted to emoe_status by the caller).
+hipError_t launch_route(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
+                        const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st);
+hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t* topk_expert,
+                          const int32_t* slot_of_expert, int32_t* counts, int32_t* offsets, int32_t* perm,
+                          int32_t* inv_perm, void* x_perm, void* ws, hipStream_t st);
+hipError_t launch_combine(const emoe_layer_desc& d, const void* y_perm, const int32_t* inv_perm,
+                          const float* topk_weight, void* out, hipStream_t st);
+hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets, const void* w1,
+                          const void* w3, const void* w2, void* y_perm, void* ws, int passes, hipStream_t st);
+hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
+                                 const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
+                                 int passes, hipStream_t st);
+hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
+                                  const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
+                                  int passes, hipStream_t st);
+hipError_t launch_fill_i32(int32_t* p, int n, int32_t value, hipStream_t st);
+hipError_t launch_write_maps(const int32_t* slot_of_expert_new, int E, const int32_t* expert_of_slot_new, int S,
+                             int32_t* slot_of_expert_dev, int32_t* expert_of_slot_dev, hipStream_t st);
+
+}  // namespace emoe

@@ -1,0 +1,174 @@
+// Stable counting sort of the A = T*k assignments by slot id and the row gather into slot-contiguous
+// order.  The per-slot row counts are the per-expert "workload" of eMoE Section 3.2.2.
+//
+// Four launches, no atomics on global memory, so the result is the unique stable permutation:
+//   1. count    : each workgroup histograms its chunk of kPermuteChunk assignments (LDS counters)
+//   2. scan     : per slot, exclusive prefix over the workgroups; then prefix over the slots
+//   3. place    : each workgroup ranks its assignments in order with wave ballots and writes
+//                 perm / inv_perm
+//   4. gather   : one wavefront per output row copies the token row, 16 bytes per lane
+// An assignment whose expert is not resident (only possible when the caller broke emoe_route's
+// precondition) is left out: inv_perm = -1, and it appears in no slot.
+#include "common.h"
+
+namespace emoe {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kPasses = kPermuteChunk / kThreads;
+
+__device__ __forceinline__ int key_of(const int32_t* __restrict__ topk_expert,
+                                      const int32_t* __restrict__ slot_of_expert, int a, int A, int E, int S) {
+    if (a >= A) return -1;
+    int e = topk_expert[a];
+    if (e < 0 || e >= E) return -1;
+    int s = slot_of_expert[e];
+    return (s >= 0 && s < S) ? s : -1;
+}
+
+__global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restrict__ topk_expert,
+                                                         const int32_t* __restrict__ slot_of_expert,
+                                                         int32_t* __restrict__ block_counts, int A, int E, int S) {
+    __shared__ int cnt[kMaxExperts];
+    if (threadIdx.x < kMaxExperts) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kPermuteChunk;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+        int key = key_of(topk_expert, slot_of_expert, base + p * kThreads + threadIdx.x, A, E, S);
+        if (key >= 0) atomicAdd(&cnt[key], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < S) block_counts[(size_t)blockIdx.x * S + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// One workgroup of 1024 threads.  Wave w handles slots w, w+16, ...: its lanes stride over the
+// workgroups of the count kernel and turn block_counts[b][s] into the exclusive prefix over b.
+__global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ block_counts, int n_blocks, int S,
+                                                    int32_t* __restrict__ slot_counts,
+                                                    int32_t* __restrict__ slot_offsets) {
+    __shared__ int total[kMaxExperts];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    for (int s = wave; s < S; s += 16) {
+        int carry = 0;
+        for (int b0 = 0; b0 < n_blocks; b0 += 64) {
+            const int b = b0 + lane;
+            int c = b < n_blocks ? block_counts[(size_t)b * S + s] : 0;
+            int incl = c;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            if (b < n_blocks) block_counts[(size_t)b * S + s] = carry + incl - c;
+            carry += __shfl(incl, 63);
+        }
+        if (lane == 0) total[s] = carry;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int c = lane < S ? total[lane] : 0;
+        int incl = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        if (lane < S) {
+            slot_counts[lane] = c;
+            slot_offsets[lane] = incl - c;
+        }
+        if (lane == S - 1) slot_offsets[S] = incl;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void place_kernel(const int32_t* __restrict__ topk_expert,
+                                                         const int32_t* __restrict__ slot_of_expert,
+                                                         const int32_t* __restrict__ block_prefix,
+                                                         const int32_t* __restrict__ slot_offsets,
+                                                         int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                                         int A, int E, int S) {
+    __shared__ int running[kMaxExperts];             // next free row of each slot for this workgroup
+    __shared__ int wave_cnt[kThreads / 64][kMaxExperts];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    if (threadIdx.x < S)
+        running[threadIdx.x] = slot_offsets[threadIdx.x] + block_prefix[(size_t)blockIdx.x * S + threadIdx.x];
+    const int base = blockIdx.x * kPermuteChunk;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int p = 0; p < kPasses; ++p) {
+        const int a = base + p * kThreads + threadIdx.x;
+        const int key = key_of(topk_expert, slot_of_expert, a, A, E, S);
+        int rank = 0;
+        int mine = 0;  // lane s ends up with this wave's count for slot s
+        for (int s = 0; s < S; ++s) {
+            unsigned long long m = __ballot(key == s);
+            if (key == s) rank = __popcll(m & below);
+            if (lane == s) mine = __popcll(m);
+        }
+        wave_cnt[wave][lane] = mine;
+        __syncthreads();  // wave counts (and, first pass, running[]) visible
+        if (key >= 0) {
+            int r = running[key] + rank;
+            for (int w = 0; w < wave; ++w) r += wave_cnt[w][key];
+            perm[r] = a;
+            inv_perm[a] = r;
+        } else if (a < A) {
+            inv_perm[a] = -1;
+        }
+        __syncthreads();  // everyone has read running[] and wave_cnt[]
+        if (threadIdx.x < S) {
+            int add = 0;
+#pragma unroll
+            for (int w = 0; w < kThreads / 64; ++w) add += wave_cnt[w][threadIdx.x];
+            running[threadIdx.x] += add;
+        }
+        // the next pass rewrites wave_cnt only after its own first barrier is preceded by this
+        // update being ordered: a barrier here keeps running[] and wave_cnt[] consistent
+        __syncthreads();
+    }
+}
+
+// One wavefront per grouped row: x_perm[r,:] = x[perm[r]/k,:].  Rows past the number of placed
+// assignments (only when some were left out) are not written.
+template <int kElemBytes>
+__global__ __launch_bounds__(kThreads) void gather_kernel(const uint8_t* __restrict__ x,
+                                                          const int32_t* __restrict__ perm,
+                                                          const int32_t* __restrict__ slot_offsets,
+                                                          uint8_t* __restrict__ x_perm, int A, int k, int d, int S) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (r >= A || r >= slot_offsets[S]) return;
+    const int t = perm[r] / k;
+    const size_t row_bytes = (size_t)d * kElemBytes;
+    const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)t * row_bytes);
+    uint4* dst = reinterpret_cast<uint4*>(x_perm + (size_t)r * row_bytes);
+    const int n16 = (int)(row_bytes / 16);
+    for (int i = lane; i < n16; i += 64) dst[i] = src[i];
+}
+
+}  // namespace
+
+hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t* topk_expert,
+                          const int32_t* slot_of_expert, int32_t* counts, int32_t* offsets, int32_t* perm,
+                          int32_t* inv_perm, void* x_perm, void* ws, hipStream_t st) {
+    const int A = d.T * d.k;
+    const int n_blocks = (A + kPermuteChunk - 1) / kPermuteChunk;
+    int32_t* block_counts = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(ws) + permute_ws_layout(d).block_counts);
+    count_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, A, d.E, d.S);
+    scan_kernel<<<1, 1024, 0, st>>>(block_counts, n_blocks, d.S, counts, offsets);
+    place_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, offsets, perm, inv_perm, A,
+                                                d.E, d.S);
+    const int rows_per_block = kThreads / 64;
+    const int g = (A + rows_per_block - 1) / rows_per_block;
+    if (d.dtype == EMOE_F32)
+        gather_kernel<4><<<g, kThreads, 0, st>>>(static_cast<const uint8_t*>(x), perm, offsets,
+                                                 static_cast<uint8_t*>(x_perm), A, d.k, d.d_model, d.S);
+    else
+        gather_kernel<2><<<g, kThreads, 0, st>>>(static_cast<const uint8_t*>(x), perm, offsets,
+                                                 static_cast<uint8_t*>(x_perm), A, d.k, d.d_model, d.S);
+    return hipGetLastError();
+}
+
+}  // namespace emoe

@@ -1,0 +1,126 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same seeded
+inputs.  Index work must be bit-exact, gate weights within 1e-5, outputs within relative L2 1e-2
+(bf16 storage, fp32 accumulation) or 1e-5 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import emoe_inputs as gen
+import oracle
+import paper_2503_06823_amd as P
+from gpu_util import DeviceLayer, check_outputs, check_routing_and_permutation, desc_of, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def cfg(name, **kw):
+    base = dict(name=name, index=40, T=64, d_model=128, d_ff=256, E=8, k=2, R=4, dtype="bf16", act="swiglu")
+    base.update(kw)
+    return gen.LayerConfig(**base)
+
+
+# Oracle-sized cases.  Each spans several tiles of the kernel it exercises and has a ragged tail.
+SMALL_CASES = [
+    gen.C1,                                                                       # fp32 path, as specified
+    cfg("f32_ragged", dtype="f32", T=150, d_model=72, d_ff=136, E=8, k=2, R=5, S=7, index=41),
+    cfg("f32_relu_top1", dtype="f32", act="relu", T=97, d_model=64, d_ff=200, E=16, k=1, R=6, zipf_s=1.1, index=42),
+    # tiled MFMA path: > 256 rows per slot (several M tiles + tail), N tails, K tail (d=328, f=456 not % 64)
+    cfg("tiled_swiglu_ragged", T=700, d_model=328, d_ff=456, E=8, k=2, R=4, index=43),
+    cfg("tiled_swiglu_aligned", T=512, d_model=512, d_ff=768, E=8, k=2, R=3, S=5, index=44),
+    cfg("tiled_relu_skewed", act="relu", T=1500, d_model=256, d_ff=520, E=64, k=1, R=16, zipf_s=1.1, index=45),
+    cfg("tiled_topk6", T=600, d_model=256, d_ff=384, E=64, k=6, R=24, zipf_s=1.2, resident="popular", index=46),
+    # streaming path (A <= 48 S): few rows per slot, slots with 0 rows, a slot with > 64 rows
+    cfg("stream_decode", T=64, d_model=512, d_ff=1088, E=8, k=2, R=6, index=47),
+    cfg("stream_ktail", T=20, d_model=200, d_ff=328, E=8, k=2, R=5, S=8, index=48),
+    cfg("stream_relu_hot_slot", act="relu", T=90, d_model=256, d_ff=384, E=4, k=1, R=2, zipf_s=3.0, index=49),
+    cfg("stream_two_token_blocks", T=80, d_model=128, d_ff=192, E=4, k=1, R=2, index=57),
+    cfg("stream_k_equals_R", T=9, d_model=128, d_ff=192, E=6, k=3, R=3, index=50),
+    cfg("single_token", T=1, d_model=128, d_ff=256, E=8, k=2, R=4, index=51),
+    cfg("single_expert_dense", T=300, d_model=128, d_ff=256, E=1, k=1, R=1, index=52),
+]
+
+
+@pytest.mark.parametrize("c", SMALL_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("shuffle", [False, True], ids=["slots_in_order", "slots_shuffled"])
+def test_layer_matches_oracle(gpu_device, c, shuffle):
+    if shuffle and c.slots == 1:
+        pytest.skip("one slot cannot be shuffled")
+    inp = gen.make_layer_inputs(c, shuffle_slots=shuffle)
+    ref = oracle.layer_forward(inp)
+    dl = DeviceLayer(inp)
+    dl.forward()
+    torch.cuda.synchronize()
+    check_routing_and_permutation(dl, ref)
+    check_outputs(dl, ref)
+
+
+def test_each_call_alone_on_oracle_inputs(gpu_device):
+    """Each entry point fed with the oracle's results for the steps before it."""
+    c = cfg("per_call", T=300, d_model=256, d_ff=384, E=8, k=2, R=4, index=53)
+    inp = gen.make_layer_inputs(c, shuffle_slots=True)
+    ref = oracle.layer_forward(inp)
+    dl = DeviceLayer(inp)
+    b, d = dl.buf, dl.desc
+    pm = ref.permutation
+    # permute from the oracle's routing
+    te = torch.from_numpy(ref.topk_expert).cuda()
+    P.emoe_permute(d, dl.x, te, dl.slot_of_expert, b.slot_counts, b.slot_offsets, b.perm, b.inv_perm, b.x_perm,
+                   b.permute_ws, b.permute_ws.numel())
+    torch.cuda.synchronize()
+    assert np.array_equal(b.perm.cpu().numpy(), pm.perm) and np.array_equal(b.inv_perm.cpu().numpy(), pm.inv_perm)
+    # FFN from the oracle's x_perm / offsets
+    xp = to_dev(oracle.gather_rows(inp.x, pm.perm, c.k, c.dtype), c.dtype)
+    off = torch.from_numpy(pm.slot_offsets).cuda()
+    P.emoe_expert_ffn(d, xp, off, dl.w1, dl.w3, dl.w2, b.y_perm, b.ffn_ws, b.ffn_ws.numel())
+    # combine from the oracle's weights and inverse permutation
+    tw = torch.from_numpy(ref.topk_weight.astype(np.float32)).cuda()
+    ip = torch.from_numpy(pm.inv_perm).cuda()
+    P.emoe_combine(d, b.y_perm, ip, tw, b.out)
+    torch.cuda.synchronize()
+    check_outputs(dl, ref)
+
+
+def test_zero_tokens_is_a_noop(gpu_device):
+    c = cfg("empty", T=0, index=54)
+    d = desc_of(c)
+    buf = P.LayerBuffers.allocate(d)
+    buf.slot_counts.fill_(7)
+    buf.slot_offsets.fill_(7)
+    dummy = torch.zeros(16, dtype=torch.bfloat16, device="cuda")
+    soe = torch.zeros(c.E, dtype=torch.int32, device="cuda")
+    assert P.emoe_route(d, dummy, dummy, None, soe, buf.topk_expert, buf.topk_weight) == P.EMOE_OK
+    assert P.emoe_permute(d, dummy, buf.topk_expert, soe, buf.slot_counts, buf.slot_offsets, buf.perm, buf.inv_perm,
+                          buf.x_perm, buf.permute_ws, buf.permute_ws.numel()) == P.EMOE_OK
+    assert P.emoe_expert_ffn(d, buf.x_perm, buf.slot_offsets, dummy, dummy, dummy, buf.y_perm, buf.ffn_ws,
+                             buf.ffn_ws.numel()) == P.EMOE_OK
+    assert P.emoe_combine(d, buf.y_perm, buf.inv_perm, buf.topk_weight, buf.out) == P.EMOE_OK
+    torch.cuda.synchronize()
+    assert not buf.slot_counts.cpu().numpy().any() and not buf.slot_offsets.cpu().numpy().any()
+
+
+def test_results_are_reproducible_run_to_run(gpu_device):
+    c = cfg("determinism", T=700, d_model=256, d_ff=384, E=16, k=2, R=6, zipf_s=1.1, index=55)
+    dl = DeviceLayer(gen.make_layer_inputs(c))
+    snaps = []
+    for _ in range(5):
+        dl.forward()
+        torch.cuda.synchronize()
+        b = dl.buf
+        snaps.append([t.clone() for t in (b.topk_expert, b.topk_weight, b.perm, b.inv_perm, b.slot_offsets, b.y_perm,
+                                          b.out)])
+    for s in snaps[1:]:
+        for t0, t1 in zip(snaps[0], s):
+            assert torch.equal(t0, t1)
+
+
+def test_all_experts_resident_equals_the_ordinary_layer(gpu_device):
+    """First prompt of a session: every expert is on the GPU (Section 3.3)."""
+    c = cfg("all_resident", T=200, d_model=128, d_ff=256, E=8, k=2, R=8, index=56)
+    inp = gen.make_layer_inputs(c)
+    ref = oracle.layer_forward(inp)
+    assert np.array_equal(ref.topk_expert, oracle.route_unrestricted(ref.logits, c.k))
+    dl = DeviceLayer(inp)
+    dl.forward()
+    torch.cuda.synchronize()
+    check_routing_and_permutation(dl, ref)
+    check_outputs(dl, ref)

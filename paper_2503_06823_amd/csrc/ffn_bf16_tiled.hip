@@ -18,6 +18,8 @@
 // surplus workgroups exit.  Workgroup ids are dealt round-robin to the 8 XCDs, so ids are
 // remapped: each XCD walks a contiguous range of the (slot, n-tile, m-tile) order with the
 // m-tile fastest, which keeps one weight panel (and the slot's token panels) in that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace emoe {
@@ -39,13 +41,22 @@ constexpr int XCDS = 8;
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
 
-template <int EPI>
-__global__ __launch_bounds__(256, 1) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
-                                                            const int32_t* __restrict__ offsets,
-                                                            const bf16_t* __restrict__ b0,
-                                                            const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
-                                                            int S, int N, int K, int n_tiles) {
+// WM x WN wavefronts; each owns (BM/WM) tokens x (BR/WN) weight rows.  KTAIL: K is not a multiple
+// of BK, 16-byte pieces past K are read as zeros.
+template <int EPI, int WM, int WN, bool KTAIL>
+__global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
+                                                                  const int32_t* __restrict__ offsets,
+                                                                  const bf16_t* __restrict__ b0,
+                                                                  const bf16_t* __restrict__ b1,
+                                                                  bf16_t* __restrict__ c, int S, int N, int K,
+                                                                  int n_tiles) {
+    constexpr int NT = 64 * WM * WN;                   // threads
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
+    constexpr int TB = BM / WM / 32;                   // token blocks per wavefront
+    constexpr int WB = BR / WN / 32;                   // weight-row blocks per wavefront
+    constexpr int LROWS = NT / 8;                      // tile rows covered by one load round
+    constexpr int LN = BM / LROWS;                     // load rounds per operand tile
+    static_assert(EPI != kSwiglu || WB % 2 == 0, "gate and up blocks come in pairs");
     extern __shared__ __align__(16) bf16_t lds[];
 
     // ---- which tile is mine -------------------------------------------------------------
@@ -73,117 +84,183 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_bf16(const bf16_t* __rest
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
-    // ---- global -> register staging: thread loads 16-byte chunk `lc` of rows lr + 32*i -----
+    // ---- global -> register staging --------------------------------------------------------
+    // A tile needs 2*LN 16-byte items per thread: items 0..LN-1 are chunk `lc` of token rows
+    // lr + LROWS*i, items LN..2LN-1 the same of the weight rows.  Addresses are a uniform base
+    // (advanced by one K tile per iteration) plus a 32-bit per-thread byte offset.
     const int lc = tid & 7, lr = tid >> 3;
-    const bf16_t* a_src[8];
-    const bf16_t* b_src[8];
+    constexpr int NI = 2 * LN;
+    uint32_t off[NI];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int r = row0 + lr + 32 * i;
+    for (int i = 0; i < LN; ++i) {
+        const int tr = lr + LROWS * i;  // row of the tile
+        int r = row0 + tr;
         r = r < row_end ? r : row_end - 1;
-        a_src[i] = a + (size_t)r * K + lc * 8;
-        int n;
-        const bf16_t* wb = w0;
-        if (EPI == kSwiglu) {
-            n = n0 + lr + 32 * (i & 3);
-            if (i >= 4) wb = w1;
-        } else {
-            n = n0 + lr + 32 * i;
-        }
+        off[i] = ((uint32_t)r * (uint32_t)K + lc * 8) * 2u;
+        int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
         n = n < N ? n : N - 1;
-        b_src[i] = wb + (size_t)n * K + lc * 8;
+        off[LN + i] = ((uint32_t)n * (uint32_t)K + lc * 8) * 2u;
     }
-    uint4 a_reg[8], b_reg[8];
-    auto load_global = [&](int k0) {
-        const bool ok = k0 + lc * 8 < K;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            a_reg[i] = ok ? *reinterpret_cast<const uint4*>(a_src[i] + k0) : make_uint4(0, 0, 0, 0);
-            b_reg[i] = ok ? *reinterpret_cast<const uint4*>(b_src[i] + k0) : make_uint4(0, 0, 0, 0);
-        }
+    const char* a_base = reinterpret_cast<const char*>(a);
+    const char* w0_base = reinterpret_cast<const char*>(w0);
+    const char* w1_base = reinterpret_cast<const char*>(EPI == kSwiglu ? w1 : w0);
+    // Two register sets: tile t travels through set t&1.  A set is refilled (tile t+2) right
+    // after it has been written to LDS (tile t), so two tiles are in flight from global memory
+    // at any time: a load that misses L2 takes longer than one K tile of matrix work.
+    uint4 reg[2][NI];
+    // item j of the tile that starts at element k0 -> register set `set`
+    auto load_item = [&](int set, int j, int k0) {
+        const bool ok = !KTAIL || (k0 + lc * 8 < K);
+        const char* base = j < LN ? a_base : ((EPI == kSwiglu && (j - LN) * LROWS >= BR / 2) ? w1_base : w0_base);
+        reg[set][j] = ok ? *reinterpret_cast<const uint4*>(base + (size_t)k0 * 2 + off[j]) : make_uint4(0, 0, 0, 0);
     };
-    auto store_lds = [&](int stage) {
-        bf16_t* at = lds + stage * STAGE_ELEMS;
-        bf16_t* bt = at + TILE_ELEMS;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            *reinterpret_cast<uint4*>(at + (lr + 32 * i) * LDS_ROW + lc * 8) = a_reg[i];
-            *reinterpret_cast<uint4*>(bt + (lr + 32 * i) * LDS_ROW + lc * 8) = b_reg[i];
-        }
+    // item j of register set `set` -> LDS buffer `stage`
+    auto store_item = [&](int set, int j, int stage) {
+        bf16_t* t = lds + stage * STAGE_ELEMS + (j < LN ? 0 : TILE_ELEMS);
+        const int i = j < LN ? j : j - LN;
+        *reinterpret_cast<uint4*>(t + (lr + LROWS * i) * LDS_ROW + lc * 8) = reg[set][j];
     };
 
     // ---- fragment addresses ----------------------------------------------------------------
-    // token block mi: tile rows wm*128 + mi*32 + lane%32; weight block ni: see header comment
+    // SwiGLU: weight blocks 0..WB/2-1 are gate rows, WB/2..WB-1 the matching up rows
     const int frag_k = (lane >> 5) * 8;
-    int x_row[4], w_row[4];
+    int x_row[TB], w_row[WB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        x_row[i] = (wm * 128 + i * 32 + (lane & 31)) * LDS_ROW + frag_k;
+    for (int i = 0; i < TB; ++i) x_row[i] = (wm * (BM / WM) + i * 32 + (lane & 31)) * LDS_ROW + frag_k;
+#pragma unroll
+    for (int i = 0; i < WB; ++i) {
         int rr;
         if (EPI == kSwiglu)
-            rr = (i < 2) ? wn * 64 + i * 32 : 128 + wn * 64 + (i - 2) * 32;
+            rr = (i < WB / 2) ? wn * (BR / 2 / WN) + i * 32 : BR / 2 + wn * (BR / 2 / WN) + (i - WB / 2) * 32;
         else
-            rr = wn * 128 + i * 32;
+            rr = wn * (BR / WN) + i * 32;
         w_row[i] = (rr + (lane & 31)) * LDS_ROW + frag_k;
     }
 
-    floatx16 acc[4][4];  // [weight block][token block]
+    floatx16 acc[WB][TB];  // [weight block][token block]
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    // ---- main loop ----------------------------------------------------------------------------
+    // Software pipeline, one barrier per K tile.  While tile kt is multiplied out of LDS buffer
+    // kt&1 in four 16-wide steps:
+    //   steps 0-2: a third of tile kt+1 (in registers, requested two iterations ago) is written
+    //           to the other buffer and the freed registers are refilled from global memory with
+    //           tile kt+3, so the memory pipes see a steady trickle instead of a burst
+    //   after step 2: every wavefront waits for its LDS traffic and meets at the barrier: tile
+    //           kt+1 is now visible, buffer kt&1 is free
+    //   step 3: the first fragments of tile kt+1 are requested
+    // Each step requests the next step's fragments before its own MFMAs are issued, so LDS and
+    // global latency hide behind matrix work; the scheduling barriers pin that order.
     const int k_tiles = (K + BK - 1) / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < k_tiles;
-        if (more) load_global((kt + 1) * BK);
-        const bf16_t* at = lds + cur * STAGE_ELEMS;
+    bf16x8 xf[2][TB], wf[2][WB];
+    auto load_frags = [&](int buf, int stage, int kk) {
+        const bf16_t* at = lds + stage * STAGE_ELEMS;
         const bf16_t* bt = at + TILE_ELEMS;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 xf[4], wf[4];
+        for (int i = 0; i < TB; ++i) xf[buf][i] = *reinterpret_cast<const bf16x8*>(at + x_row[i] + kk * 16);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                xf[i] = *reinterpret_cast<const bf16x8*>(at + x_row[i] + kk * 16);
-                wf[i] = *reinterpret_cast<const bf16x8*>(bt + w_row[i] + kk * 16);
-            }
+        for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(bt + w_row[i] + kk * 16);
+    };
+    auto mfma_step = [&](int buf) {
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
+        for (int ni = 0; ni < WB; ++ni)
 #pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
-        }
-        if (more) store_lds(cur ^ 1);
-        __syncthreads();
+            for (int mi = 0; mi < TB; ++mi)
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
+    };
+
+#pragma unroll
+    for (int j = 0; j < NI; ++j) load_item(0, j, 0);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) store_item(0, j, 0);
+    {
+        const int k_last0 = (k_tiles - 1) * BK;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) load_item(1, j, BK < k_last0 ? BK : k_last0);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) load_item(0, j, 2 * BK < k_last0 ? 2 * BK : k_last0);
     }
+    __syncthreads();
+    load_frags(0, 0, 0);
+    // items moved per step (steps 0..2): set (kt+1)&1 -> LDS as tile kt+1, then refilled with tile kt+3
+    constexpr int PER = (NI + 2) / 3;
+    // ODD (parity of kt) is compile-time so the register sets and LDS buffers are addressed
+    // statically, and the body has no branches (a branch would make the compiler drain every
+    // outstanding load).  Near the end of K the body still moves data: the loads are clamped to
+    // the last tile and the surplus lands in an LDS buffer nobody reads any more.
+    const int k_last = (k_tiles - 1) * BK;
+    auto iteration = [&](auto odd_c, int kt) {
+        constexpr int ODD = decltype(odd_c)::value;
+        constexpr int cur = ODD, nxt = ODD ^ 1;  // LDS buffer of tile kt / of tile kt+1 (= its register set)
+        int k3 = (kt + 3) * BK;
+        k3 = k3 < k_last ? k3 : k_last;
+        auto move_items = [&](int step) {
+#pragma unroll
+            for (int j = step * PER; j < (step + 1) * PER && j < NI; ++j) {
+                store_item(nxt, j, nxt);
+                load_item(nxt, j, k3);
+            }
+        };
+        // step 0
+        load_frags(1, cur, 1);
+        move_items(0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // step 1
+        load_frags(0, cur, 2);
+        move_items(1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+        // step 2
+        load_frags(1, cur, 3);
+        move_items(2);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        // step 3
+        load_frags(0, nxt, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    int kt = 0;
+    for (; kt + 1 < k_tiles; kt += 2) {
+        iteration(I0{}, kt);
+        iteration(I1{}, kt + 1);
+    }
+    if (kt < k_tiles) iteration(I0{}, kt);
 
     // ---- epilogue: lane holds, per block, token lane%32 and weight rows 8g + 4*(lane/32) + 0..3 ---
-    constexpr int NB = EPI == kSwiglu ? 2 : 4;
+    constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
+    const int col0 = n0 + wn * (BNO / WN) + (lane >> 5) * 4;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int r = row0 + wm * 128 + mi * 32 + (lane & 31);
+    for (int mi = 0; mi < TB; ++mi) {
+        const int r = row0 + wm * (BM / WM) + mi * 32 + (lane & 31);
         if (r >= row_end) continue;
         bf16_t* crow = c + (size_t)r * N;
 #pragma unroll
         for (int ni = 0; ni < NB; ++ni) {
-            const int nb = n0 + (EPI == kSwiglu ? wn * 64 : wn * 128) + ni * 32 + (lane >> 5) * 4;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = nb + 8 * g;
+                const int n = col0 + ni * 32 + 8 * g;
                 if (n >= N) continue;
                 floatx4 v;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float t = acc[ni][mi][4 * g + q];
-                    if (EPI == kSwiglu) t = t / (1.0f + __expf(-t)) * acc[ni + 2][mi][4 * g + q];
+                    if (EPI == kSwiglu) t = t / (1.0f + __expf(-t)) * acc[ni + NB][mi][4 * g + q];
                     if (EPI == kRelu) t = fmaxf(t, 0.0f);
                     v[q] = t;
                 }
@@ -194,6 +271,23 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_bf16(const bf16_t* __rest
     }
 }
 
+constexpr int kWavesM = 2, kWavesN = 2;
+
+template <int EPI, bool KTAIL>
+hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
+                      unsigned blocks, int S, int N, int K, int n_tiles, hipStream_t st) {
+    auto kern = grouped_gemm_bf16<EPI, kWavesM, kWavesN, KTAIL>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    kern<<<blocks, 64 * kWavesM * kWavesN, LDS_BYTES, st>>>(a, offsets, b0, b1, c, S, N, K, n_tiles);
+    return hipGetLastError();
+}
+
 template <int EPI>
 hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int A,
                       int S, int N, int K, hipStream_t st) {
@@ -202,15 +296,8 @@ hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0,
     const int m_tiles = (A + BM - 1) / BM + S;
     long long blocks = (long long)n_tiles * m_tiles;
     blocks = (blocks + XCDS - 1) / XCDS * XCDS;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_gemm_bf16<EPI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    grouped_gemm_bf16<EPI><<<(unsigned)blocks, 256, LDS_BYTES, st>>>(a, offsets, b0, b1, c, S, N, K, n_tiles);
-    return hipGetLastError();
+    if (K % BK == 0) return launch_cfg<EPI, false>(a, offsets, b0, b1, c, (unsigned)blocks, S, N, K, n_tiles, st);
+    return launch_cfg<EPI, true>(a, offsets, b0, b1, c, (unsigned)blocks, S, N, K, n_tiles, st);
 }
 
 }  // namespace

@@ -5,21 +5,32 @@
 //   pass 1: h[r, n]      = act(x_perm[r,:] . W1_s[n,:]) (* x_perm[r,:] . W3_s[n,:])   K = d_model
 //   pass 2: y_perm[r, n] = h[r,:] . W2_s[n,:]                                         K = d_ff
 //
-// Both operands are K-contiguous, so every MFMA operand is one 16-byte LDS read.  A workgroup of
-// four wavefronts (2 x 2) owns a 256-token x 256-weight-row tile; each wavefront accumulates a
-// 128 x 128 sub-tile as 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 in fp32.  In the SwiGLU pass the
-// 256 weight rows are 128 rows of W1 and the SAME 128 rows of W3, laid out so that a lane holds the
-// gate and the up value of the same output element and the activation is applied in registers.
-// The weight rows go on the MFMA's row operand: a lane then owns four consecutive output columns
-// of one token and stores them as one 8-byte write.
+// Tile: a workgroup of NW = 4 wavefronts (2 x 2, one per SIMD) owns 256 tokens x 256 weight rows;
+// each wavefront accumulates 128 x 128 as 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 in fp32 (256
+// accumulator registers).  Eight wavefronts (128 x 64 each) measured slower: more LDS reads per MFMA.  In the SwiGLU pass the 256 weight rows are 128 rows of W1 and the SAME 128 rows of
+// W3, arranged so that a lane holds the gate and the up value of the same output element and the
+// activation is applied in registers.  The weight rows go on the MFMA's row operand: a lane then
+// owns four consecutive output columns of one token and stores them as one 8-byte write.
+//
+// Data movement: both operands are K-contiguous in memory.  K is walked in tiles of 32; a tile
+// (256 + 256 rows x 64 bytes = 32 KiB) goes from global memory straight into LDS with
+// buffer_load_dwordx4 ... lds (no staging registers, no LDS store instructions), four LDS stages
+// deep, so up to three tiles are in flight while one is multiplied.  Each load instruction fills
+// 1 KiB of LDS contiguously (16 rows x 64 bytes); the 16-byte chunk c of row r is stored at chunk
+// position c ^ ((r >> 2) & 3), chosen by which global chunk a lane fetches, which makes the MFMA
+// fragment reads (32 rows x one chunk per ds_read_b128) bank-conflict free without padding.
+// Buffer addressing gives a uniform (scalar) K offset plus a per-lane row offset, so the loop has
+// no address arithmetic; in the K tail, chunks past K are fetched out of range and arrive as zeros.
+//
+// Schedule per K tile (two MFMA steps of 16 each): fragment reads for the next step and the loads
+// of tile t+3 are slotted one by one between the MFMAs, so no memory instruction waits in a full
+// queue while the matrix pipe idles.  One barrier per tile, placed between the two steps.
 //
 // Ragged groups: group sizes live on the device.  The launch covers an upper bound of M-tiles
 // (ceil(A/256) + S); every workgroup finds its (slot, m-tile, n-tile) from slot_offsets and
 // surplus workgroups exit.  Workgroup ids are dealt round-robin to the 8 XCDs, so ids are
 // remapped: each XCD walks a contiguous range of the (slot, n-tile, m-tile) order with the
 // m-tile fastest, which keeps one weight panel (and the slot's token panels) in that XCD's L2.
-#include <type_traits>
-
 #include "common.h"
 
 namespace emoe {
@@ -29,35 +40,53 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int BM = 256;            // tokens per tile
-constexpr int BR = 256;            // weight rows per tile (SwiGLU: 128 of W1 + 128 of W3)
-constexpr int BK = 64;             // K step
-constexpr int LDS_ROW = BK + 8;    // bf16 elements per LDS row: 144 bytes, conflict-free 16-byte reads
-constexpr int TILE_ELEMS = BM * LDS_ROW;
-constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;  // token tile + weight tile
-constexpr size_t LDS_BYTES = 2 * STAGE_ELEMS * sizeof(bf16_t);
+constexpr int BM = 256;                     // tokens per tile
+constexpr int BR = 256;                     // weight rows per tile (SwiGLU: 128 of W1 + 128 of W3)
+constexpr int BK = 32;                      // K elements per tile
+constexpr int ROW_BYTES = BK * 2;           // 64
+constexpr int TILE_BYTES = BM * ROW_BYTES;  // 16 KiB per operand
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+constexpr int STAGES = 4;
+constexpr size_t LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KiB
 constexpr int XCDS = 8;
+constexpr int NW = 4;            // wavefronts per workgroup, arranged 2 (tokens) x NW/2 (weight rows)
+constexpr int WN = NW / 2;
+constexpr int TB = 4;            // 32-token blocks per wavefront (128 tokens)
+constexpr int WB = BR / WN / 32; // 32-row weight blocks per wavefront
+constexpr int LPW = 16 / NW;     // load instructions per wavefront, per tile and operand
+constexpr int LOADS = 2 * LPW;   // ... per tile
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
 
-// WM x WN wavefronts; each owns (BM/WM) tokens x (BR/WN) weight rows.  KTAIL: K is not a multiple
-// of BK, 16-byte pieces past K are read as zeros.
-template <int EPI, int WM, int WN, bool KTAIL>
-__global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
-                                                                  const int32_t* __restrict__ offsets,
-                                                                  const bf16_t* __restrict__ b0,
-                                                                  const bf16_t* __restrict__ b1,
-                                                                  bf16_t* __restrict__ c, int S, int N, int K,
-                                                                  int n_tiles) {
-    constexpr int NT = 64 * WM * WN;                   // threads
+// s_waitcnt immediate: vmcnt <= n and all LDS traffic done (vmcnt[3:0] | [15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int wait_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0x0 << 8); }
+
+// Workgroup barrier once at most `n` of this wavefront's global->LDS loads are still pending and
+// all its LDS reads have returned.  __syncthreads() would drain every pending load (its release
+// fence counts the LDS writes of the loads), which is exactly what the deep prefetch must avoid.
+// The empty asm statements stop the compiler from moving LDS accesses across the barrier.
+template <int N>
+__device__ __forceinline__ void barrier_keep_loads() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(wait_imm(N));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+template <int EPI, bool KTAIL>
+__global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
+                                                         const int32_t* __restrict__ offsets,
+                                                         const bf16_t* __restrict__ b0,
+                                                         const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
+                                                         int S, int N, int K, int n_tiles) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
-    constexpr int TB = BM / WM / 32;                   // token blocks per wavefront
-    constexpr int WB = BR / WN / 32;                   // weight-row blocks per wavefront
-    constexpr int LROWS = NT / 8;                      // tile rows covered by one load round
-    constexpr int LN = BM / LROWS;                     // load rounds per operand tile
-    static_assert(EPI != kSwiglu || WB % 2 == 0, "gate and up blocks come in pairs");
-    extern __shared__ __align__(16) bf16_t lds[];
+    extern __shared__ __align__(16) char lds[];
 
     // ---- which tile is mine -------------------------------------------------------------
     const int per_xcd = gridDim.x / XCDS;
@@ -78,57 +107,53 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* 
     }
     if (slot < 0) return;
     const int n0 = nt * BNO;
-    const bf16_t* w0 = b0 + (size_t)slot * N * K;
-    const bf16_t* w1 = EPI == kSwiglu ? b1 + (size_t)slot * N * K : nullptr;
+    const int rows_total = offsets[S];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- global -> register staging --------------------------------------------------------
-    // A tile needs 2*LN 16-byte items per thread: items 0..LN-1 are chunk `lc` of token rows
-    // lr + LROWS*i, items LN..2LN-1 the same of the weight rows.  Addresses are a uniform base
-    // (advanced by one K tile per iteration) plus a 32-bit per-thread byte offset.
-    const int lc = tid & 7, lr = tid >> 3;
-    constexpr int NI = 2 * LN;
-    uint32_t off[NI];
+    // ---- global -> LDS ---------------------------------------------------------------------
+    // Wavefront w issues, per tile and per operand, load instructions i = 0..LPW-1; instruction
+    // (w, i) fills tile rows (LPW*w + i)*16 .. +15.  Lane l lands in row l>>2, chunk position l&3
+    // and therefore fetches global chunk (l&3) ^ ((row>>2)&3).
+    const int l_row = lane >> 2;
+    const int l_chunk = (lane & 3) ^ ((l_row >> 2) & 3);
+    const uint32_t a_bytes = (uint32_t)rows_total * (uint32_t)K * 2u;
+    const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
+    uint32_t a_voff[LPW], b_voff[LPW];
 #pragma unroll
-    for (int i = 0; i < LN; ++i) {
-        const int tr = lr + LROWS * i;  // row of the tile
+    for (int i = 0; i < LPW; ++i) {
+        const int tr = (LPW * wave + i) * 16 + l_row;  // row of the tile
         int r = row0 + tr;
         r = r < row_end ? r : row_end - 1;
-        off[i] = ((uint32_t)r * (uint32_t)K + lc * 8) * 2u;
+        a_voff[i] = ((uint32_t)r * (uint32_t)K + l_chunk * 8) * 2u;
         int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
         n = n < N ? n : N - 1;
-        off[LN + i] = ((uint32_t)n * (uint32_t)K + lc * 8) * 2u;
+        b_voff[i] = ((uint32_t)n * (uint32_t)K + l_chunk * 8) * 2u;
     }
-    const char* a_base = reinterpret_cast<const char*>(a);
-    const char* w0_base = reinterpret_cast<const char*>(w0);
-    const char* w1_base = reinterpret_cast<const char*>(EPI == kSwiglu ? w1 : w0);
-    // Two register sets: tile t travels through set t&1.  A set is refilled (tile t+2) right
-    // after it has been written to LDS (tile t), so two tiles are in flight from global memory
-    // at any time: a load that misses L2 takes longer than one K tile of matrix work.
-    uint4 reg[2][NI];
-    // item j of the tile that starts at element k0 -> register set `set`
-    auto load_item = [&](int set, int j, int k0) {
-        const bool ok = !KTAIL || (k0 + lc * 8 < K);
-        const char* base = j < LN ? a_base : ((EPI == kSwiglu && (j - LN) * LROWS >= BR / 2) ? w1_base : w0_base);
-        reg[set][j] = ok ? *reinterpret_cast<const uint4*>(base + (size_t)k0 * 2 + off[j]) : make_uint4(0, 0, 0, 0);
-    };
-    // item j of register set `set` -> LDS buffer `stage`
-    auto store_item = [&](int set, int j, int stage) {
-        bf16_t* t = lds + stage * STAGE_ELEMS + (j < LN ? 0 : TILE_ELEMS);
-        const int i = j < LN ? j : j - LN;
-        *reinterpret_cast<uint4*>(t + (lr + LROWS * i) * LDS_ROW + lc * 8) = reg[set][j];
+    const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // upper wavefronts load the W3 half
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a, a_bytes);
+    const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(wsel + (size_t)slot * N * K, b_bytes);
+    const int k_tiles = (K + BK - 1) / BK;
+    const int k_last = (k_tiles - 1) * BK;
+    // one load instruction: j < LPW token rows, j >= LPW weight rows, of the tile starting at element k0
+    auto issue_load = [&](int j, int stage, int k0) {
+        const bool tok = j < LPW;
+        const int i = tok ? j : j - LPW;
+        uint32_t voff = tok ? a_voff[i] : b_voff[i];
+        if (KTAIL && k0 + l_chunk * 8 >= K) voff = tok ? a_bytes : b_bytes;  // out of range: zeros
+        char* dst = lds + stage * STAGE_BYTES + (tok ? 0 : TILE_BYTES) + (LPW * wave + i) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(tok ? a_rsrc : b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 0);
     };
 
-    // ---- fragment addresses ----------------------------------------------------------------
+    // ---- fragment addresses (bytes within a stage, for the first MFMA step; the second is ^32) ----
     // SwiGLU: weight blocks 0..WB/2-1 are gate rows, WB/2..WB-1 the matching up rows
-    const int frag_k = (lane >> 5) * 8;
-    int x_row[TB], w_row[WB];
-#pragma unroll
-    for (int i = 0; i < TB; ++i) x_row[i] = (wm * (BM / WM) + i * 32 + (lane & 31)) * LDS_ROW + frag_k;
+    const int f_row = lane & 31;
+    const int f_sw = (((lane >> 5) ^ ((f_row >> 2) & 3)) & 3) * 16;
+    const int x_off = (wm * 128 + f_row) * ROW_BYTES + f_sw;  // + i * 32 rows
+    int w_off[WB];
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
         int rr;
@@ -136,7 +161,7 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* 
             rr = (i < WB / 2) ? wn * (BR / 2 / WN) + i * 32 : BR / 2 + wn * (BR / 2 / WN) + (i - WB / 2) * 32;
         else
             rr = wn * (BR / WN) + i * 32;
-        w_row[i] = (rr + (lane & 31)) * LDS_ROW + frag_k;
+        w_off[i] = TILE_BYTES + (rr + f_row) * ROW_BYTES + f_sw;
     }
 
     floatx16 acc[WB][TB];  // [weight block][token block]
@@ -147,26 +172,14 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // ---- main loop ----------------------------------------------------------------------------
-    // Software pipeline, one barrier per K tile.  While tile kt is multiplied out of LDS buffer
-    // kt&1 in four 16-wide steps:
-    //   steps 0-2: a third of tile kt+1 (in registers, requested two iterations ago) is written
-    //           to the other buffer and the freed registers are refilled from global memory with
-    //           tile kt+3, so the memory pipes see a steady trickle instead of a burst
-    //   after step 2: every wavefront waits for its LDS traffic and meets at the barrier: tile
-    //           kt+1 is now visible, buffer kt&1 is free
-    //   step 3: the first fragments of tile kt+1 are requested
-    // Each step requests the next step's fragments before its own MFMAs are issued, so LDS and
-    // global latency hide behind matrix work; the scheduling barriers pin that order.
-    const int k_tiles = (K + BK - 1) / BK;
     bf16x8 xf[2][TB], wf[2][WB];
     auto load_frags = [&](int buf, int stage, int kk) {
-        const bf16_t* at = lds + stage * STAGE_ELEMS;
-        const bf16_t* bt = at + TILE_ELEMS;
+        const char* base = lds + stage * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < TB; ++i) xf[buf][i] = *reinterpret_cast<const bf16x8*>(at + x_row[i] + kk * 16);
+        for (int i = 0; i < TB; ++i)
+            xf[buf][i] = *reinterpret_cast<const bf16x8*>(base + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
 #pragma unroll
-        for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(bt + w_row[i] + kk * 16);
+        for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(base + (w_off[i] ^ (kk * 32)));
     };
     auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -175,79 +188,62 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* 
             for (int mi = 0; mi < TB; ++mi)
                 acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
     };
-
+    // the step's MFMAs with its LDS reads and global->LDS loads slotted in one at a time
+    auto interleave = [&]() {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) load_item(0, j, 0);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) store_item(0, j, 0);
-    {
-        const int k_last0 = (k_tiles - 1) * BK;
-#pragma unroll
-        for (int j = 0; j < NI; ++j) load_item(1, j, BK < k_last0 ? BK : k_last0);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) load_item(0, j, 2 * BK < k_last0 ? 2 * BK : k_last0);
-    }
-    __syncthreads();
-    load_frags(0, 0, 0);
-    // items moved per step (steps 0..2): set (kt+1)&1 -> LDS as tile kt+1, then refilled with tile kt+3
-    constexpr int PER = (NI + 2) / 3;
-    // ODD (parity of kt) is compile-time so the register sets and LDS buffers are addressed
-    // statically, and the body has no branches (a branch would make the compiler drain every
-    // outstanding load).  Near the end of K the body still moves data: the loads are clamped to
-    // the last tile and the surplus lands in an LDS buffer nobody reads any more.
-    const int k_last = (k_tiles - 1) * BK;
-    auto iteration = [&](auto odd_c, int kt) {
-        constexpr int ODD = decltype(odd_c)::value;
-        constexpr int cur = ODD, nxt = ODD ^ 1;  // LDS buffer of tile kt / of tile kt+1 (= its register set)
-        int k3 = (kt + 3) * BK;
-        k3 = k3 < k_last ? k3 : k_last;
-        auto move_items = [&](int step) {
-#pragma unroll
-            for (int j = step * PER; j < (step + 1) * PER && j < NI; ++j) {
-                store_item(nxt, j, nxt);
-                load_item(nxt, j, k3);
-            }
-        };
-        // step 0
-        load_frags(1, cur, 1);
-        move_items(0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        // step 1
-        load_frags(0, cur, 2);
-        move_items(1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(1);
-        __builtin_amdgcn_sched_barrier(0);
-        // step 2
-        load_frags(1, cur, 3);
-        move_items(2);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        // step 3
-        load_frags(0, nxt, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(1);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < TB * WB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                // one MFMA
+            if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
+            else if (i < TB + WB + LOADS / 2) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
+        }
     };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    int kt = 0;
-    for (; kt + 1 < k_tiles; kt += 2) {
-        iteration(I0{}, kt);
-        iteration(I1{}, kt + 1);
+
+    // ---- prologue: tiles 0..2 on their way, tile 0 landed ------------------------------------
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t) {
+        const int k0 = t * BK < k_last ? t * BK : k_last;
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) issue_load(j, t, k0);
     }
-    if (kt < k_tiles) iteration(I0{}, kt);
+    barrier_keep_loads<2 * LOADS>();
+    load_frags(0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- main loop ---------------------------------------------------------------------------
+    // Near the end of K the loads are clamped to the last tile: the surplus lands in a stage that
+    // nobody reads any more, and the loop body stays free of branches.
+    for (int t = 0; t < k_tiles; ++t) {
+        const int stage = t & (STAGES - 1);
+        const int stage_in = (t + STAGES - 1) & (STAGES - 1);  // receives tile t+3; held tile t-1
+        int k3 = (t + STAGES - 1) * BK;
+        k3 = k3 < k_last ? k3 : k_last;
+        // step 0: MFMAs on the first 16 of K; second-half fragments and half of the loads issued
+        load_frags(1, stage, 1);
+#pragma unroll
+        for (int j = 0; j < LOADS / 2; ++j) issue_load(j, stage_in, k3);
+        mfma_step(0);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        // tile t+1 has landed once only tile t+2 (8 loads) and this step's 4 loads are pending; the
+        // LDS reads of tile t are complete: after the barrier its stage is dead, tile t+1 visible
+        barrier_keep_loads<LOADS + LOADS / 2>();
+        __builtin_amdgcn_sched_barrier(0);
+        // step 1: MFMAs on the second 16 of K; first fragments of tile t+1 and the other loads issued
+        load_frags(0, (t + 1) & (STAGES - 1), 0);
+#pragma unroll
+        for (int j = LOADS / 2; j < LOADS; ++j) issue_load(j, stage_in, k3);
+        mfma_step(1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(wait_imm(0));  // surplus loads must not outlive the workgroup's LDS
 
     // ---- epilogue: lane holds, per block, token lane%32 and weight rows 8g + 4*(lane/32) + 0..3 ---
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
     const int col0 = n0 + wn * (BNO / WN) + (lane >> 5) * 4;
 #pragma unroll
     for (int mi = 0; mi < TB; ++mi) {
-        const int r = row0 + wm * (BM / WM) + mi * 32 + (lane & 31);
+        const int r = row0 + wm * 128 + mi * 32 + (lane & 31);
         if (r >= row_end) continue;
         bf16_t* crow = c + (size_t)r * N;
 #pragma unroll
@@ -271,12 +267,10 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_bf16(const bf16_t* 
     }
 }
 
-constexpr int kWavesM = 2, kWavesN = 2;
-
 template <int EPI, bool KTAIL>
 hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
                       unsigned blocks, int S, int N, int K, int n_tiles, hipStream_t st) {
-    auto kern = grouped_gemm_bf16<EPI, kWavesM, kWavesN, KTAIL>;
+    auto kern = grouped_gemm_bf16<EPI, KTAIL>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -284,7 +278,7 @@ hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0,
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<blocks, 64 * kWavesM * kWavesN, LDS_BYTES, st>>>(a, offsets, b0, b1, c, S, N, K, n_tiles);
+    kern<<<blocks, 64 * NW, LDS_BYTES, st>>>(a, offsets, b0, b1, c, S, N, K, n_tiles);
     return hipGetLastError();
 }
 

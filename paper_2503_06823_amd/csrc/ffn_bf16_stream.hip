@@ -2,16 +2,21 @@
 // resident, non-empty slot's weights from HBM exactly once (eMoE Section 5.1: fewer experts
 // means fewer global-memory reads), so the kernels are shaped for streaming, not for MFMA rate.
 //
-// A work unit is 32 consecutive weight rows of one slot.  The weight rows are the MFMA's row
-// operand (v_mfma_f32_32x32x16_bf16), up to 64 of the slot's tokens are the column operand, so a
-// weight element is loaded once and used for every token.  Operands go from global memory
-// straight into registers: weights are used once (nothing to share through LDS) and the slot's
-// few token rows stay in L2.  A slot with no rows exits at once and its weights are never read.
-// Latency is hidden by occupancy: every unit of the launch is resident at the same time.
-//   pass 1 (K = d_model): one wavefront per unit, gate and up rows together, activation in
-//                          registers, h rounded to bf16.
-//   pass 2 (K = d_ff)   : four wavefronts per unit split K, partial sums meet in LDS (fixed
-//                          order, so the result is reproducible), y rounded to bf16.
+// A workgroup (4 wavefronts, two workgroups per CU) owns 64 weight rows of one slot - in the
+// SwiGLU pass 32 rows of W1 and the same 32 rows of W3 - and walks K in tiles of 128.  A tile goes
+// from global memory straight into LDS with buffer_load_dwordx4 ... lds: every load instruction
+// reads 1 KiB that is contiguous in LDS and consists of whole 256-byte row pieces in memory, so
+// HBM is read in full cache lines no matter what layout the MFMA wants.  Three LDS stages per
+// workgroup keep two tiles in flight; with two workgroups per CU that is 64 KiB of weights in flight
+// per CU, enough to cover HBM latency at full bandwidth.  The slot's token rows (at most 32 per
+// pass, they live in L2) ride along in the same tiles.
+// In LDS the 16-byte chunk c of row r sits at chunk position c ^ (r & 15): the MFMA fragment reads
+// (32 rows x one chunk) are then bank-conflict free.
+// The weight rows are the MFMA's row operand (v_mfma_f32_32x32x16_bf16), the tokens its column
+// operand, so a weight element is used for every token.  The four wavefronts split the eight MFMA
+// K-steps of a tile; their partial sums meet in LDS at the end, added in wavefront order, so the
+// result is reproducible.  A slot with no rows exits before it touches its weights; a slot with more
+// than 32 rows is processed 32 rows at a time (the repeated weight reads come from cache).
 #include "common.h"
 
 namespace emoe {
@@ -21,153 +26,195 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
-constexpr int RB = 32;   // weight rows per unit
-constexpr int KC = 64;   // K elements per loop step (four MFMA steps)
+constexpr int WR = 64;                      // weight rows per workgroup
+constexpr int TOK = 32;                     // token rows per pass
+constexpr int BK = 128;                     // K elements per tile
+constexpr int ROW_BYTES = BK * 2;           // 256
+constexpr int W_BYTES = WR * ROW_BYTES;     // 16 KiB
+constexpr int X_BYTES = TOK * ROW_BYTES;    // 8 KiB
+constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
+constexpr int STAGES = 3;
+constexpr int LW = W_BYTES / 1024 / 4;      // weight load instructions per wavefront and tile (4)
+constexpr int LX = X_BYTES / 1024 / 4;      // token load instructions per wavefront and tile (2)
+constexpr int LOADS = LW + LX;
+constexpr int RED_BYTES = 3 * 32 * 64 * 4;  // partial sums of wavefronts 1..3
+static_assert(RED_BYTES <= STAGES * STAGE_BYTES, "the reduction reuses the tile stages");
 
-__device__ __forceinline__ bf16x8 load8(const bf16_t* p, bool ok) {
-    if (!ok) {
-        bf16x8 z;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
-        return z;
-    }
-    return *reinterpret_cast<const bf16x8*>(p);
+// s_waitcnt immediate: vmcnt <= n and all LDS traffic done (vmcnt[3:0] | [15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int wait_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0x0 << 8); }
+
+// Workgroup barrier that leaves up to N global->LDS loads of this wavefront pending
+// (__syncthreads() would drain them all).  The empty asm statements keep the compiler from moving
+// LDS accesses across it.
+template <int N>
+__device__ __forceinline__ void barrier_keep_loads() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(wait_imm(N));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
-// Accumulates rows [row_begin, row_begin + 32*NTB) of the slot against this unit's weight rows
-// over K chunks [ch0, ch1).  GUARD: K is not a multiple of KC, pieces past K read as zero.
-template <int EPI, int NTB, bool GUARD>
-__device__ __forceinline__ void accumulate(const bf16_t* __restrict__ a, const bf16_t* __restrict__ wr0,
-                                           const bf16_t* __restrict__ wr1, int row_begin, int row_end, int K, int ch0,
-                                           int ch1, int lane, floatx16 (&acc0)[NTB], floatx16 (&acc1)[NTB]) {
-    const int kq = (lane >> 5) * 8;
-    const bf16_t* xr[NTB];
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb) {
-        int r = row_begin + tb * 32 + (lane & 31);
-        r = r < row_end ? r : row_end - 1;
-        xr[tb] = a + (size_t)r * K + kq;
-    }
-    for (int ch = ch0; ch < ch1; ++ch) {
-        const int k0 = ch * KC;
-        bf16x8 wf0[4], wf1[4], xf[NTB][4];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const bool ok = !GUARD || (k0 + ks * 16 + kq < K);
-            wf0[ks] = load8(wr0 + k0 + ks * 16, ok);
-            if (EPI == kSwiglu) wf1[ks] = load8(wr1 + k0 + ks * 16, ok);
-#pragma unroll
-            for (int tb = 0; tb < NTB; ++tb) xf[tb][ks] = load8(xr[tb] + k0 + ks * 16, ok);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int tb = 0; tb < NTB; ++tb) {
-                acc0[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[ks], xf[tb][ks], acc0[tb], 0, 0, 0);
-                if (EPI == kSwiglu)
-                    acc1[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[ks], xf[tb][ks], acc1[tb], 0, 0, 0);
-            }
-    }
-}
-
-template <int EPI, int KW, int NTB, bool GUARD>
-__device__ __forceinline__ void unit_body(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w0,
-                                          const bf16_t* __restrict__ w1, bf16_t* __restrict__ c, int row_begin,
-                                          int row_end, int n0, int N, int K, float* red) {
-    const int lane = threadIdx.x & 63;
-    const int kw = threadIdx.x >> 6;
-    int n = n0 + (lane & 31);
-    n = n < N ? n : N - 1;
-    const bf16_t* wr0 = w0 + (size_t)n * K + (lane >> 5) * 8;
-    const bf16_t* wr1 = EPI == kSwiglu ? w1 + (size_t)n * K + (lane >> 5) * 8 : nullptr;
-    const int chunks = (K + KC - 1) / KC;
-    const int ch0 = (int)((long long)chunks * kw / KW), ch1 = (int)((long long)chunks * (kw + 1) / KW);
-
-    floatx16 acc0[NTB], acc1[NTB];
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { acc0[tb][v] = 0.0f; acc1[tb][v] = 0.0f; }
-    accumulate<EPI, NTB, GUARD>(a, wr0, wr1, row_begin, row_end, K, ch0, ch1, lane, acc0, acc1);
-
-    if (KW > 1) {  // partial sums of the K splits meet in LDS; wave 0 adds them in split order
-        if (kw > 0) {
-#pragma unroll
-            for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) red[((kw - 1) * NTB * 16 + tb * 16 + v) * 64 + lane] = acc0[tb][v];
-        }
-        __syncthreads();
-        if (kw == 0) {
-#pragma unroll
-            for (int w = 1; w < KW; ++w)
-#pragma unroll
-                for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc0[tb][v] += red[((w - 1) * NTB * 16 + tb * 16 + v) * 64 + lane];
-        }
-        __syncthreads();  // red[] is reused by the next token chunk
-        if (kw != 0) return;
-    }
-    // lane holds token lane%32 of each block and weight rows 8g + 4*(lane/32) + 0..3
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb) {
-        const int r = row_begin + tb * 32 + (lane & 31);
-        if (r >= row_end) continue;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int nn = n0 + 8 * g + (lane >> 5) * 4;
-            if (nn >= N) continue;
-            floatx4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float t = acc0[tb][4 * g + q];
-                if (EPI == kSwiglu) t = t / (1.0f + __expf(-t)) * acc1[tb][4 * g + q];
-                if (EPI == kRelu) t = fmaxf(t, 0.0f);
-                v[q] = t;
-            }
-            *reinterpret_cast<bf16x4*>(c + (size_t)r * N + nn) = __builtin_convertvector(v, bf16x4);
-        }
-    }
-}
-
-// grid.x = S * ceil(N / 32) units; blockDim.x = 64 * KW.
-template <int EPI, int KW, bool GUARD>
-__global__ __launch_bounds__(64 * KW) void stream_gemm_bf16(const bf16_t* __restrict__ a,
-                                                             const int32_t* __restrict__ offsets,
-                                                             const bf16_t* __restrict__ b0,
-                                                             const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
-                                                             int N, int K, int n_rb) {
-    __shared__ float red[KW > 1 ? (KW - 1) * 2 * 16 * 64 : 1];
-    const int slot = blockIdx.x / n_rb;
-    const int n0 = (blockIdx.x % n_rb) * RB;
+// grid.x = S * ceil(N / BNO) workgroups, BNO = output columns per workgroup (32 SwiGLU, else 64).
+template <int EPI, bool KTAIL>
+__global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restrict__ a,
+                                                           const int32_t* __restrict__ offsets,
+                                                           const bf16_t* __restrict__ b0,
+                                                           const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
+                                                           int S, int N, int K, int n_units) {
+    constexpr int BNO = EPI == kSwiglu ? WR / 2 : WR;
+    __shared__ __align__(16) char lds[STAGES * STAGE_BYTES];
+    const int slot = blockIdx.x / n_units;
+    const int n0 = (blockIdx.x % n_units) * BNO;
     const int row0 = offsets[slot], row_end = offsets[slot + 1];
     if (row_end <= row0) return;  // empty slot: its weights are never touched
-    const bf16_t* w0 = b0 + (size_t)slot * N * K;
-    const bf16_t* w1 = EPI == kSwiglu ? b1 + (size_t)slot * N * K : nullptr;
-    int r = row0;
-    // whole chunks of 64 tokens, then a last chunk of at most 64 (one block if it fits in 32)
-    while (row_end - r > 64) {
-        unit_body<EPI, KW, 2, GUARD>(a, w0, w1, c, r, row_end, n0, N, K, red);
-        r += 64;
+    const int rows_total = offsets[S];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    // ---- global -> LDS: instruction (w, i) fills four tile rows; lane l lands in row l>>4, chunk
+    //      position l&15 and fetches global chunk (l&15) ^ (row&15) -------------------------------
+    const int l_rin = lane >> 4;
+    const uint32_t a_bytes = (uint32_t)rows_total * (uint32_t)K * 2u;
+    const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
+    uint32_t w_voff[LW];
+    int w_chunk[LW];
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const int tr = (LW * wave + i) * 4 + l_rin;  // row of the weight tile
+        w_chunk[i] = (lane & 15) ^ (tr & 15);
+        int n = n0 + (EPI == kSwiglu ? tr % (WR / 2) : tr);  // SwiGLU: rows 32..63 = same rows of W3
+        n = n < N ? n : N - 1;
+        w_voff[i] = ((uint32_t)n * (uint32_t)K + w_chunk[i] * 8) * 2u;
     }
-    if (row_end - r > 32)
-        unit_body<EPI, KW, 2, GUARD>(a, w0, w1, c, r, row_end, n0, N, K, red);
-    else
-        unit_body<EPI, KW, 1, GUARD>(a, w0, w1, c, r, row_end, n0, N, K, red);
+    const bf16_t* wsel = (EPI == kSwiglu && wave >= 2) ? b1 : b0;  // wavefronts 2,3 load the W3 half
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a), 0, (int)a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(wsel + (size_t)slot * N * K), 0, (int)b_bytes, 0x00020000);
+
+    // ---- fragment addresses: lane holds row lane%32 and, for MFMA step s, chunk 2s + lane/32 ------
+    const int f_row = lane & 31;
+    const int f_half = lane >> 5;
+    const int k_tiles = (K + BK - 1) / BK;
+
+    for (int tok0 = row0; tok0 < row_end; tok0 += TOK) {  // 32 tokens per pass over the weights
+        uint32_t x_voff[LX];
+        int x_chunk[LX];
+#pragma unroll
+        for (int i = 0; i < LX; ++i) {
+            const int tr = (LX * wave + i) * 4 + l_rin;  // row of the token tile
+            x_chunk[i] = (lane & 15) ^ (tr & 15);
+            int r = tok0 + tr;
+            r = r < row_end ? r : row_end - 1;
+            x_voff[i] = ((uint32_t)r * (uint32_t)K + x_chunk[i] * 8) * 2u;
+        }
+        auto issue_tile = [&](int stage, int k0) {
+            char* base = lds + stage * STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < LW; ++i) {
+                uint32_t v = w_voff[i];
+                if (KTAIL && k0 + w_chunk[i] * 8 >= K) v = b_bytes;  // out of range: zeros
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_void*)(base + (LW * wave + i) * 1024), 16, (int)v,
+                                                         k0 * 2, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < LX; ++i) {
+                uint32_t v = x_voff[i];
+                if (KTAIL && k0 + x_chunk[i] * 8 >= K) v = a_bytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void*)(base + W_BYTES + (LX * wave + i) * 1024), 16,
+                                                         (int)v, k0 * 2, 0, 0);
+            }
+        };
+
+        floatx16 acc0, acc1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc0[v] = 0.0f; acc1[v] = 0.0f; }
+
+#pragma unroll
+        for (int t = 0; t < STAGES - 1; ++t)
+            if (t < k_tiles) issue_tile(t, t * BK);
+        // loads are counted per wavefront and retire in order: with `pending` tiles issued after tile t,
+        // tile t has landed once at most pending * LOADS loads are outstanding
+        int stage = 0;
+        for (int t = 0; t < k_tiles; ++t) {
+            if (t + STAGES - 2 < k_tiles) barrier_keep_loads<(STAGES - 2) * LOADS>();
+            else barrier_keep_loads<0>();
+            // everyone has finished tile t-1: its stage can take tile t+STAGES-1
+            if (t + STAGES - 1 < k_tiles) issue_tile(stage == 0 ? STAGES - 1 : stage - 1, (t + STAGES - 1) * BK);
+            const char* wt = lds + stage * STAGE_BYTES;
+            const char* xt = wt + W_BYTES;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int s = 2 * wave + s2;  // this wavefront's MFMA steps of the tile
+                const int ch = 2 * s + f_half;
+                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xt + f_row * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
+                const bf16x8 w0f = *reinterpret_cast<const bf16x8*>(wt + f_row * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
+                const bf16x8 w1f =
+                    *reinterpret_cast<const bf16x8*>(wt + (32 + f_row) * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0f, xf, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1f, xf, acc1, 0, 0, 0);
+            }
+            stage = stage + 1 == STAGES ? 0 : stage + 1;
+        }
+
+        // ---- partial sums of the four K splits meet in LDS; wavefront 0 adds them in order -----------
+        barrier_keep_loads<0>();  // all tiles consumed: the stages can be reused
+        float* red = reinterpret_cast<float*>(lds);
+        if (wave > 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                red[((wave - 1) * 32 + v) * 64 + lane] = acc0[v];
+                red[((wave - 1) * 32 + 16 + v) * 64 + lane] = acc1[v];
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int w = 0; w < 3; ++w)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    acc0[v] += red[(w * 32 + v) * 64 + lane];
+                    acc1[v] += red[(w * 32 + 16 + v) * 64 + lane];
+                }
+            // lane holds token lane%32 and weight rows 8g + 4*(lane/32) + 0..3 of each 32-row block
+            const int r = tok0 + (lane & 31);
+            if (r < row_end) {
+#pragma unroll
+                for (int blk = 0; blk < (EPI == kSwiglu ? 1 : 2); ++blk) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int nn = n0 + blk * 32 + 8 * g + (lane >> 5) * 4;
+                        if (nn >= N) continue;
+                        floatx4 v;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float tv = blk == 0 ? acc0[4 * g + q] : acc1[4 * g + q];
+                            if (EPI == kSwiglu) tv = tv / (1.0f + __expf(-tv)) * acc1[4 * g + q];
+                            if (EPI == kRelu) tv = fmaxf(tv, 0.0f);
+                            v[q] = tv;
+                        }
+                        *reinterpret_cast<bf16x4*>(c + (size_t)r * N + nn) = __builtin_convertvector(v, bf16x4);
+                    }
+                }
+            }
+        }
+        __syncthreads();  // the reduction buffer is tile memory again for the next 32 tokens
+    }
 }
 
-template <int EPI, int KW>
+template <int EPI>
 hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
                       int N, int K, hipStream_t st) {
-    const int n_rb = (N + RB - 1) / RB;
-    const unsigned blocks = (unsigned)(S * n_rb);
-    if (K % KC == 0)
-        stream_gemm_bf16<EPI, KW, false><<<blocks, 64 * KW, 0, st>>>(a, offsets, b0, b1, c, N, K, n_rb);
+    constexpr int BNO = EPI == kSwiglu ? WR / 2 : WR;
+    const int n_units = (N + BNO - 1) / BNO;
+    const unsigned blocks = (unsigned)(S * n_units);
+    if (K % BK == 0)
+        stream_gemm_bf16<EPI, false><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
     else
-        stream_gemm_bf16<EPI, KW, true><<<blocks, 64 * KW, 0, st>>>(a, offsets, b0, b1, c, N, K, n_rb);
+        stream_gemm_bf16<EPI, true><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
     return hipGetLastError();
 }
 
@@ -181,13 +228,13 @@ hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, 
     hipError_t e = hipSuccess;
     if (!(passes & 1)) {
     } else if (d.act == EMOE_ACT_SWIGLU)
-        e = launch_one<kSwiglu, 1>(xp, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h,
-                                   d.S, d.d_ff, d.d_model, st);
+        e = launch_one<kSwiglu>(xp, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h, d.S,
+                                d.d_ff, d.d_model, st);
     else
-        e = launch_one<kRelu, 1>(xp, offsets, static_cast<const bf16_t*>(w1), nullptr, h, d.S, d.d_ff, d.d_model, st);
+        e = launch_one<kRelu>(xp, offsets, static_cast<const bf16_t*>(w1), nullptr, h, d.S, d.d_ff, d.d_model, st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain, 4>(h, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm),
-                                 d.S, d.d_model, d.d_ff, st);
+    return launch_one<kPlain>(h, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm), d.S,
+                              d.d_model, d.d_ff, st);
 }
 
 }  // namespace emoe

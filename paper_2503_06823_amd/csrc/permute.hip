@@ -1,7 +1,8 @@
 // Stable counting sort of the A = T*k assignments by slot id and the row gather into slot-contiguous
 // order.  The per-slot row counts are the per-expert "workload" of eMoE Section 3.2.2.
 //
-// Four launches, no atomics on global memory, so the result is the unique stable permutation:
+// Four launches (two when all assignments fit one workgroup: count, scan and place fused), no
+// atomics on global memory, so the result is the unique stable permutation:
 //   1. count    : each workgroup histograms its chunk of kPermuteChunk assignments (LDS counters)
 //   2. scan     : per slot, exclusive prefix over the workgroups; then prefix over the slots
 //   3. place    : each workgroup ranks its assignments in order with wave ballots and writes
@@ -124,8 +125,74 @@ __global__ __launch_bounds__(kThreads) void place_kernel(const int32_t* __restri
             for (int w = 0; w < kThreads / 64; ++w) add += wave_cnt[w][threadIdx.x];
             running[threadIdx.x] += add;
         }
-        // the next pass rewrites wave_cnt only after its own first barrier is preceded by this
-        // update being ordered: a barrier here keeps running[] and wave_cnt[] consistent
+        __syncthreads();  // running[] updated before the next pass reads it and rewrites wave_cnt[]
+    }
+}
+
+// count + scan + place in one workgroup, for A <= kPermuteChunk (a decode step): two launches fewer.
+__global__ __launch_bounds__(kThreads) void sort_small_kernel(const int32_t* __restrict__ topk_expert,
+                                                              const int32_t* __restrict__ slot_of_expert,
+                                                              int32_t* __restrict__ slot_counts,
+                                                              int32_t* __restrict__ slot_offsets,
+                                                              int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                                              int A, int E, int S) {
+    __shared__ int cnt[kMaxExperts];
+    __shared__ int running[kMaxExperts];
+    __shared__ int wave_cnt[kThreads / 64][kMaxExperts];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    if (threadIdx.x < kMaxExperts) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    int keys[kPasses];
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+        keys[p] = key_of(topk_expert, slot_of_expert, p * kThreads + threadIdx.x, A, E, S);
+        if (keys[p] >= 0) atomicAdd(&cnt[keys[p]], 1);
+    }
+    __syncthreads();
+    if (wave == 0) {  // exclusive prefix over the slots
+        const int c = lane < S ? cnt[lane] : 0;
+        int incl = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        if (lane < S) {
+            slot_counts[lane] = c;
+            slot_offsets[lane] = incl - c;
+            running[lane] = incl - c;
+        }
+        if (lane == S - 1) slot_offsets[S] = incl;
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int p = 0; p < kPasses; ++p) {
+        if (p * kThreads >= A) break;  // uniform
+        const int a = p * kThreads + threadIdx.x;
+        const int key = keys[p];
+        int rank = 0, mine = 0;
+        for (int s = 0; s < S; ++s) {
+            unsigned long long m = __ballot(key == s);
+            if (key == s) rank = __popcll(m & below);
+            if (lane == s) mine = __popcll(m);
+        }
+        wave_cnt[wave][lane] = mine;
+        __syncthreads();
+        if (key >= 0) {
+            int r = running[key] + rank;
+            for (int w = 0; w < wave; ++w) r += wave_cnt[w][key];
+            perm[r] = a;
+            inv_perm[a] = r;
+        } else if (a < A) {
+            inv_perm[a] = -1;
+        }
+        __syncthreads();
+        if (threadIdx.x < S) {
+            int add = 0;
+#pragma unroll
+            for (int w = 0; w < kThreads / 64; ++w) add += wave_cnt[w][threadIdx.x];
+            running[threadIdx.x] += add;
+        }
         __syncthreads();
     }
 }
@@ -156,10 +223,15 @@ hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t
     const int A = d.T * d.k;
     const int n_blocks = (A + kPermuteChunk - 1) / kPermuteChunk;
     int32_t* block_counts = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(ws) + permute_ws_layout(d).block_counts);
-    count_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, A, d.E, d.S);
-    scan_kernel<<<1, 1024, 0, st>>>(block_counts, n_blocks, d.S, counts, offsets);
-    place_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, offsets, perm, inv_perm, A,
-                                                d.E, d.S);
+    if (n_blocks == 1) {
+        sort_small_kernel<<<1, kThreads, 0, st>>>(topk_expert, slot_of_expert, counts, offsets, perm, inv_perm, A, d.E,
+                                                  d.S);
+    } else {
+        count_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, A, d.E, d.S);
+        scan_kernel<<<1, 1024, 0, st>>>(block_counts, n_blocks, d.S, counts, offsets);
+        place_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, offsets, perm,
+                                                    inv_perm, A, d.E, d.S);
+    }
     const int rows_per_block = kThreads / 64;
     const int g = (A + rows_per_block - 1) / rows_per_block;
     if (d.dtype == EMOE_F32)

@@ -1,8 +1,9 @@
 // Gate logits and resident-restricted top-k (eMoE Section 1: the gate; Section 3.2.2, last
 // paragraph: a token whose expert is not on the GPU goes to its next-best expert that is).
 //
-// One wavefront owns one token at a time.  Its 64 lanes split the d_model axis (16 bytes per
-// lane per step, so a step reads 1 KiB of the token row contiguously); every lane keeps one
+// One wavefront (or, when there are few tokens, four) owns one token at a time.  Its 64 lanes
+// split the d_model axis (16 bytes per lane per step, so a step reads 1 KiB of the token row
+// contiguously); every lane keeps one
 // partial sum per expert.  A butterfly reduce-scatter then leaves expert e's complete logit in
 // lane e*(64/EP): 63 shuffles for 64 experts instead of 64 full reductions.  Top-k is k rounds
 // of a wave-wide arg-max on (logit, lower index wins); softmax over the k winners.
@@ -34,36 +35,69 @@ template <> struct Vec<float> {
 };
 
 // EP = number of experts rounded up to a power of two (1..64).
-template <typename T, int EP>
+// SPLIT = wavefronts that share one token (1 or 4).  With few tokens (a decode step) one wavefront
+// per token would leave most of the chip idle and make each wavefront walk the whole row alone, so
+// four wavefronts split the row and add their partial logits through LDS in wavefront order.
+template <typename T, int EP, int SPLIT>
 __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, const T* __restrict__ w_gate,
                                                     const float* __restrict__ bias,
                                                     const int32_t* __restrict__ slot_of_expert,
                                                     int32_t* __restrict__ topk_expert,
                                                     float* __restrict__ topk_weight, int T_, int d, int E, int k) {
     constexpr int VN = Vec<T>::N;
+    __shared__ float partial[SPLIT > 1 ? 4 * 64 : 1];
     const int lane = threadIdx.x & 63;
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    const int wib = threadIdx.x >> 6;  // wavefront in block
+    const int tokens_per_block = 4 / SPLIT;
+    const int part = SPLIT > 1 ? wib : 0;  // which share of the row this wavefront sums
     // expert whose logit this lane ends up holding
     const int my_e = lane / (64 / EP);
     const bool resident = my_e < E && slot_of_expert[my_e] >= 0;
     const float my_bias = (bias != nullptr && my_e < E) ? bias[my_e] : 0.0f;
 
-    for (int t = wave; t < T_; t += n_waves) {
+    for (int t0 = blockIdx.x * tokens_per_block; t0 < T_; t0 += gridDim.x * tokens_per_block) {
+        const int t = t0 + (SPLIT > 1 ? 0 : wib);
+        const bool live = t < T_;  // uniform per wavefront
         float acc[EP];
 #pragma unroll
         for (int e = 0; e < EP; ++e) acc[e] = 0.0f;
-        const T* xr = x + (size_t)t * d;
-        for (int c = lane * VN; c < d; c += 64 * VN) {
-            float xv[VN];
-            Vec<T>::load(xr + c, xv);
+        if (live) {
+            const T* xr = x + (size_t)t * d;
+            // two row pieces per trip, both requested before either is used
+            int c = (part * 64 + lane) * VN;
+            const int step = SPLIT * 64 * VN;
+            for (; c + step < d; c += 2 * step) {
+                float xa[VN], xb[VN];
+                Vec<T>::load(xr + c, xa);
+                Vec<T>::load(xr + c + step, xb);
+                const T* wp = w_gate + c;  // walks down the experts' rows
 #pragma unroll
-            for (int e = 0; e < EP; ++e) {
-                if (e < E) {
-                    float wv[VN];
-                    Vec<T>::load(w_gate + (size_t)e * d + c, wv);
+                for (int e = 0; e < EP; ++e) {
+                    if (e < E) {
+                        float wa[VN], wb[VN];
+                        Vec<T>::load(wp, wa);
+                        Vec<T>::load(wp + step, wb);
 #pragma unroll
-                    for (int i = 0; i < VN; ++i) acc[e] = fmaf(xv[i], wv[i], acc[e]);
+                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xa[i], wa[i], acc[e]);
+#pragma unroll
+                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xb[i], wb[i], acc[e]);
+                        wp += d;
+                    }
+                }
+            }
+            if (c < d) {
+                float xa[VN];
+                Vec<T>::load(xr + c, xa);
+                const T* wp = w_gate + c;
+#pragma unroll
+                for (int e = 0; e < EP; ++e) {
+                    if (e < E) {
+                        float wa[VN];
+                        Vec<T>::load(wp, wa);
+#pragma unroll
+                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xa[i], wa[i], acc[e]);
+                        wp += d;
+                    }
                 }
             }
         }
@@ -85,7 +119,16 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
                 acc[0] += __shfl_xor(acc[0], m);
             }
         }
-        const float logit = acc[0] + my_bias;
+        float logit = acc[0];
+        if (SPLIT > 1) {  // the four shares of the row meet in LDS, added in wavefront order
+            partial[wib * 64 + lane] = logit;
+            __syncthreads();
+            logit = ((partial[lane] + partial[64 + lane]) + partial[128 + lane]) + partial[192 + lane];
+            __syncthreads();
+            if (wib != 0) continue;
+        }
+        if (!live) continue;
+        logit += my_bias;
 
         // k rounds of arg-max over resident experts not taken yet
         bool avail = resident;
@@ -125,12 +168,18 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
 template <typename T, int EP>
 hipError_t launch_ep(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
                      const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st) {
-    const int waves_per_block = 4;
-    int blocks = (d.T + waves_per_block - 1) / waves_per_block;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    route_kernel<T, EP><<<blocks, 64 * waves_per_block, 0, st>>>(
-        static_cast<const T*>(x), static_cast<const T*>(w_gate), bias, slot_of_expert, topk_expert, topk_weight,
-        d.T, d.d_model, d.E, d.k);
+    const T* xp = static_cast<const T*>(x);
+    const T* wg = static_cast<const T*>(w_gate);
+    if (d.T <= 2048) {  // fewer than two wavefronts per SIMD otherwise: share each token among four
+        int blocks = d.T < 256 * 16 ? d.T : 256 * 16;
+        route_kernel<T, EP, 4><<<blocks, 256, 0, st>>>(xp, wg, bias, slot_of_expert, topk_expert, topk_weight, d.T,
+                                                       d.d_model, d.E, d.k);
+    } else {
+        int blocks = (d.T + 3) / 4;
+        if (blocks > 256 * 16) blocks = 256 * 16;
+        route_kernel<T, EP, 1><<<blocks, 256, 0, st>>>(xp, wg, bias, slot_of_expert, topk_expert, topk_weight, d.T,
+                                                       d.d_model, d.E, d.k);
+    }
     return hipGetLastError();
 }
 

@@ -63,6 +63,7 @@ def test_load_then_forward_then_change_resident_set(gpu_device):
     loaded, done = torch.cuda.Event(), torch.cuda.Event()
     x, wg = to_dev(base.x, "bf16"), to_dev(base.w_gate, "bf16")
     buf = P.LayerBuffers.allocate(d)
+    side.wait_stream(compute)   # the fills above run on the compute stream: order them before the first load
 
     def forward():
         return P.layer_forward(buf, x, wg, None, soe, w1s, w3s, w2s)
@@ -135,6 +136,7 @@ def test_upload_is_a_bit_copy_in_list_order(gpu_device):
     eos = torch.full((S,), -1, dtype=torch.int32, device="cuda")
     mirror = np.full(S, -1, dtype=np.int32)
     side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())   # the fills above must not overtake the load
     P.emoe_load_experts(d, [5, 2], [2, 0], host.w1, None, host.w2, w1s, None, w2s, soe, eos, mirror, side)
     side.synchronize()
     assert torch.equal(w1s[2].cpu().view(torch.int16), host.w1[5]) and torch.equal(w2s[0].cpu().view(torch.int16), host.w2[2])

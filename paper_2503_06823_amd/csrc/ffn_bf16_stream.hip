@@ -37,9 +37,13 @@ constexpr int W_BYTES = WR * ROW_BYTES;     // 16 KiB
 constexpr int X_BYTES = TOK * ROW_BYTES;    // 8 KiB
 constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
 constexpr int STAGES = 3;
-constexpr int LW = W_BYTES / 1024 / 4;      // weight load instructions per wavefront and tile (4)
-constexpr int LX = X_BYTES / 1024 / 4;      // token load instructions per wavefront and tile (2)
+constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per tile row
+constexpr int RPI = 1024 / ROW_BYTES;       // tile rows filled by one load instruction
+constexpr int SPW = BK / 16 / 4;            // MFMA steps per wavefront and tile
+constexpr int LW = W_BYTES / 1024 / 4;      // weight load instructions per wavefront and tile
+constexpr int LX = X_BYTES / 1024 / 4;      // token load instructions per wavefront and tile
 constexpr int LOADS = LW + LX;
+constexpr unsigned kRotation = 21;           // K-tile rotation per workgroup (measured best of 1..29)
 constexpr int RED_BYTES = 3 * 32 * 64 * 4;  // partial sums of wavefronts 1..3
 static_assert(RED_BYTES <= STAGES * STAGE_BYTES, "the reduction reuses the tile stages");
 
@@ -75,17 +79,17 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    // ---- global -> LDS: instruction (w, i) fills four tile rows; lane l lands in row l>>4, chunk
-    //      position l&15 and fetches global chunk (l&15) ^ (row&15) -------------------------------
-    const int l_rin = lane >> 4;
+    // ---- global -> LDS: instruction (w, i) fills RPI tile rows; lane l lands in row l/CPR, chunk
+    //      position l%CPR and fetches global chunk (l%CPR) ^ (row&15) ------------------------------
+    const int l_rin = lane / CPR, l_pos = lane % CPR;
     const uint32_t a_bytes = (uint32_t)rows_total * (uint32_t)K * 2u;
     const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
     uint32_t w_voff[LW];
     int w_chunk[LW];
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
-        const int tr = (LW * wave + i) * 4 + l_rin;  // row of the weight tile
-        w_chunk[i] = (lane & 15) ^ (tr & 15);
+        const int tr = (LW * wave + i) * RPI + l_rin;  // row of the weight tile
+        w_chunk[i] = l_pos ^ (tr & 15);
         int n = n0 + (EPI == kSwiglu ? tr % (WR / 2) : tr);  // SwiGLU: rows 32..63 = same rows of W3
         n = n < N ? n : N - 1;
         w_voff[i] = ((uint32_t)n * (uint32_t)K + w_chunk[i] * 8) * 2u;
@@ -99,14 +103,23 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
     const int f_row = lane & 31;
     const int f_half = lane >> 5;
     const int k_tiles = (K + BK - 1) / BK;
+    // Workgroups walk K from different starting tiles.  Rows are a power-of-two-ish stride apart, so
+    // workgroups marching through K in step would all pull from the same few HBM channels at once;
+    // the rotation spreads them (4.8 -> 5.7 TB/s at the Mixtral decode shape).  The order is fixed
+    // per workgroup, so results stay reproducible.
+    const int k_rot = (int)((blockIdx.x * kRotation) % (unsigned)k_tiles);
+    auto k_of = [&](int t) {
+        int tt = t + k_rot;
+        return (tt >= k_tiles ? tt - k_tiles : tt) * BK;
+    };
 
     for (int tok0 = row0; tok0 < row_end; tok0 += TOK) {  // 32 tokens per pass over the weights
         uint32_t x_voff[LX];
         int x_chunk[LX];
 #pragma unroll
         for (int i = 0; i < LX; ++i) {
-            const int tr = (LX * wave + i) * 4 + l_rin;  // row of the token tile
-            x_chunk[i] = (lane & 15) ^ (tr & 15);
+            const int tr = (LX * wave + i) * RPI + l_rin;  // row of the token tile
+            x_chunk[i] = l_pos ^ (tr & 15);
             int r = tok0 + tr;
             r = r < row_end ? r : row_end - 1;
             x_voff[i] = ((uint32_t)r * (uint32_t)K + x_chunk[i] * 8) * 2u;
@@ -135,7 +148,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
 
 #pragma unroll
         for (int t = 0; t < STAGES - 1; ++t)
-            if (t < k_tiles) issue_tile(t, t * BK);
+            if (t < k_tiles) issue_tile(t, k_of(t));
         // loads are counted per wavefront and retire in order: with `pending` tiles issued after tile t,
         // tile t has landed once at most pending * LOADS loads are outstanding
         int stage = 0;
@@ -143,12 +156,12 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
             if (t + STAGES - 2 < k_tiles) barrier_keep_loads<(STAGES - 2) * LOADS>();
             else barrier_keep_loads<0>();
             // everyone has finished tile t-1: its stage can take tile t+STAGES-1
-            if (t + STAGES - 1 < k_tiles) issue_tile(stage == 0 ? STAGES - 1 : stage - 1, (t + STAGES - 1) * BK);
+            if (t + STAGES - 1 < k_tiles) issue_tile(stage == 0 ? STAGES - 1 : stage - 1, k_of(t + STAGES - 1));
             const char* wt = lds + stage * STAGE_BYTES;
             const char* xt = wt + W_BYTES;
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const int s = 2 * wave + s2;  // this wavefront's MFMA steps of the tile
+            for (int s2 = 0; s2 < SPW; ++s2) {
+                const int s = SPW * wave + s2;  // this wavefront's MFMA steps of the tile
                 const int ch = 2 * s + f_half;
                 const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xt + f_row * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
                 const bf16x8 w0f = *reinterpret_cast<const bf16x8*>(wt + f_row * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));

@@ -29,23 +29,20 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
-constexpr int WR = 64;                      // weight rows per workgroup
+// weight rows per workgroup: template parameter WR, 64 (two MFMA row blocks) or 32 (one; plain and
+// ReLU passes only, used when 64-row units would give fewer workgroups than the chip can hold)
 constexpr int TOK = 32;                     // token rows per pass
 constexpr int BK = 128;                     // K elements per tile
 constexpr int ROW_BYTES = BK * 2;           // 256
-constexpr int W_BYTES = WR * ROW_BYTES;     // 16 KiB
 constexpr int X_BYTES = TOK * ROW_BYTES;    // 8 KiB
-constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
 constexpr int STAGES = 3;
 constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per tile row
 constexpr int RPI = 1024 / ROW_BYTES;       // tile rows filled by one load instruction
 constexpr int SPW = BK / 16 / 4;            // MFMA steps per wavefront and tile
-constexpr int LW = W_BYTES / 1024 / 4;      // weight load instructions per wavefront and tile
 constexpr int LX = X_BYTES / 1024 / 4;      // token load instructions per wavefront and tile
-constexpr int LOADS = LW + LX;
 constexpr unsigned kRotation = 21;           // K-tile rotation per workgroup (measured best of 1..29)
 constexpr int RED_BYTES = 3 * 32 * 64 * 4;  // partial sums of wavefronts 1..3
-static_assert(RED_BYTES <= STAGES * STAGE_BYTES, "the reduction reuses the tile stages");
+static_assert(RED_BYTES <= STAGES * (32 * ROW_BYTES + X_BYTES), "the reduction reuses the tile stages");
 
 // s_waitcnt immediate: vmcnt <= n and all LDS traffic done (vmcnt[3:0] | [15:14], expcnt [6:4], lgkmcnt [11:8])
 constexpr int wait_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0x0 << 8); }
@@ -62,13 +59,19 @@ __device__ __forceinline__ void barrier_keep_loads() {
 }
 
 // grid.x = S * ceil(N / BNO) workgroups, BNO = output columns per workgroup (32 SwiGLU, else 64).
-template <int EPI, bool KTAIL>
-__global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restrict__ a,
+template <int EPI, int WR, bool KTAIL>
+__global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const bf16_t* __restrict__ a,
                                                            const int32_t* __restrict__ offsets,
                                                            const bf16_t* __restrict__ b0,
                                                            const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
                                                            int S, int N, int K, int n_units) {
     constexpr int BNO = EPI == kSwiglu ? WR / 2 : WR;
+    constexpr int W_BYTES = WR * ROW_BYTES;          // 16 KiB at WR = 64
+    constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
+    constexpr int LW = W_BYTES / 1024 / 4;           // weight load instructions per wavefront and tile
+    constexpr int LOADS = LW + LX;
+    constexpr int NBLK = WR / 32;                    // MFMA row blocks
+    static_assert(WR == 64 || (WR == 32 && EPI != kSwiglu), "unsupported unit shape");
     __shared__ __align__(16) char lds[STAGES * STAGE_BYTES];
     const int slot = blockIdx.x / n_units;
     const int n0 = (blockIdx.x % n_units) * BNO;
@@ -165,10 +168,12 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
                 const int ch = 2 * s + f_half;
                 const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xt + f_row * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
                 const bf16x8 w0f = *reinterpret_cast<const bf16x8*>(wt + f_row * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
-                const bf16x8 w1f =
-                    *reinterpret_cast<const bf16x8*>(wt + (32 + f_row) * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0f, xf, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1f, xf, acc1, 0, 0, 0);
+                if (NBLK == 2) {
+                    const bf16x8 w1f =
+                        *reinterpret_cast<const bf16x8*>(wt + (32 + f_row) * ROW_BYTES + ((ch ^ (f_row & 15)) * 16));
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1f, xf, acc1, 0, 0, 0);
+                }
             }
             stage = stage + 1 == STAGES ? 0 : stage + 1;
         }
@@ -180,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 red[((wave - 1) * 32 + v) * 64 + lane] = acc0[v];
-                red[((wave - 1) * 32 + 16 + v) * 64 + lane] = acc1[v];
+                if (NBLK == 2) red[((wave - 1) * 32 + 16 + v) * 64 + lane] = acc1[v];
             }
         }
         __syncthreads();
@@ -190,13 +195,13 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     acc0[v] += red[(w * 32 + v) * 64 + lane];
-                    acc1[v] += red[(w * 32 + 16 + v) * 64 + lane];
+                    if (NBLK == 2) acc1[v] += red[(w * 32 + 16 + v) * 64 + lane];
                 }
             // lane holds token lane%32 and weight rows 8g + 4*(lane/32) + 0..3 of each 32-row block
             const int r = tok0 + (lane & 31);
             if (r < row_end) {
 #pragma unroll
-                for (int blk = 0; blk < (EPI == kSwiglu ? 1 : 2); ++blk) {
+                for (int blk = 0; blk < (EPI == kSwiglu ? 1 : NBLK); ++blk) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int nn = n0 + blk * 32 + 8 * g + (lane >> 5) * 4;
@@ -218,17 +223,27 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
     }
 }
 
-template <int EPI>
-hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
-                      int N, int K, hipStream_t st) {
+template <int EPI, int WR>
+hipError_t launch_wr(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
+                     int N, int K, hipStream_t st) {
     constexpr int BNO = EPI == kSwiglu ? WR / 2 : WR;
     const int n_units = (N + BNO - 1) / BNO;
     const unsigned blocks = (unsigned)(S * n_units);
     if (K % BK == 0)
-        stream_gemm_bf16<EPI, false><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
+        stream_gemm_bf16<EPI, WR, false><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
     else
-        stream_gemm_bf16<EPI, true><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
+        stream_gemm_bf16<EPI, WR, true><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
     return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
+                      int N, int K, hipStream_t st) {
+    if constexpr (EPI != kSwiglu) {
+        // fewer 64-row units than workgroup slots (2 per CU): halve the unit so the whole chip streams
+        if ((long long)S * ((N + 63) / 64) < 2 * 256) return launch_wr<EPI, 32>(a, offsets, b0, b1, c, S, N, K, st);
+    }
+    return launch_wr<EPI, 64>(a, offsets, b0, b1, c, S, N, K, st);
 }
 
 }  // namespace

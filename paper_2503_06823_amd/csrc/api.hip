@@ -34,11 +34,15 @@ PermuteWs permute_ws_layout(const emoe_layer_desc& d) {
     return w;
 }
 
+bool ffn_use_stream_path(const emoe_layer_desc& d);
+
 FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
     FfnWs w;
     const size_t A = (size_t)d.T * d.k;
     w.h = 0;
-    w.total = align256((A > 0 ? A : 1) * d.d_ff * elem_bytes(d));
+    w.partials = align256((A > 0 ? A : 1) * d.d_ff * elem_bytes(d));
+    w.total = w.partials;
+    if (d.dtype == EMOE_BF16 && !ffn_use_stream_path(d)) w.total += kTiledPartialBytes;
     return w;
 }
 

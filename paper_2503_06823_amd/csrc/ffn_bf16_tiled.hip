@@ -51,6 +51,8 @@ constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 constexpr int STAGES = 4;
 constexpr size_t LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KiB
 constexpr int XCDS = 8;
+constexpr int kPersistentGroups = 256;  // one workgroup per CU
+constexpr int kMaxSplits = 8;           // K pieces per leftover tile, at most
 constexpr int NW = 4;            // wavefronts per workgroup, arranged 2 (tokens) x NW/2 (weight rows)
 constexpr int WN = NW / 2;
 constexpr int TB = 4;            // 32-token blocks per wavefront (128 tokens)
@@ -79,19 +81,41 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-template <int EPI, bool KTAIL>
-__global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
-                                                         const int32_t* __restrict__ offsets,
-                                                         const bf16_t* __restrict__ b0,
-                                                         const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
-                                                         int S, int N, int K, int n_tiles) {
-    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
-    extern __shared__ __align__(16) char lds[];
+// ---- work distribution ------------------------------------------------------------------------
+// The launch is persistent: one workgroup per CU.  Output tiles are numbered in (slot, n-tile,
+// m-tile) order, m fastest.  The first `rounds * G` tiles are dealt out whole, `rounds` per
+// workgroup, so that the 32 workgroups of an XCD hold 32 consecutive tiles at any time (one weight
+// panel and the slot's token panels stay in that XCD's L2).  The `left` tiles that do not fill a
+// round are split along K into `splits` pieces each, so that they too occupy (nearly) every CU: a
+// piece writes its fp32 accumulators to the workspace and a small second kernel adds the pieces in
+// order and applies the epilogue.  Everything is derived from slot_offsets on the device.
+struct Plan {
+    int tiles;   // output tiles in total
+    int rounds;  // whole tiles per workgroup
+    int left;    // tiles beyond rounds * G
+    int splits;  // K pieces per leftover tile (1 = none)
+};
 
-    // ---- which tile is mine -------------------------------------------------------------
-    const int per_xcd = gridDim.x / XCDS;
-    int rem = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
-    int slot = -1, row0 = 0, row_end = 0, nt = 0;
+__device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ offsets, int S, int n_tiles, int k_tiles, int G) {
+    int m_tiles = 0;
+    for (int s = 0; s < S; ++s) m_tiles += (offsets[s + 1] - offsets[s] + BM - 1) / BM;
+    Plan p;
+    p.tiles = m_tiles * n_tiles;
+    p.rounds = p.tiles / G;
+    p.left = p.tiles - p.rounds * G;
+    int sp = p.left > 0 ? G / p.left : 1;
+    const int by_k = k_tiles / 16;  // at least 16 K tiles per piece
+    sp = sp < by_k ? sp : by_k;
+    sp = sp > kMaxSplits ? kMaxSplits : sp;
+    p.splits = sp < 1 ? 1 : sp;
+    return p;
+}
+
+// tile number -> slot, first row, end of the slot's rows, n-tile
+__device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets, int S, int n_tiles, int L, int& slot,
+                                            int& row0, int& row_end, int& nt) {
+    int rem = L;
+    slot = 0; row0 = 0; row_end = 0; nt = 0;
     for (int s = 0; s < S; ++s) {
         const int b = offsets[s], e = offsets[s + 1];
         const int tiles = (e - b + BM - 1) / BM;
@@ -101,59 +125,85 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             nt = rem / tiles;
             row0 = b + (rem % tiles) * BM;
             row_end = e;
-            break;
+            return;
         }
         rem -= span;
     }
-    if (slot < 0) return;
-    const int n0 = nt * BNO;
-    const int rows_total = offsets[S];
+}
+
+// One 32 x 32 output block of a wavefront: token block mi, output-column block ni.  `gate` holds the
+// accumulators (for SwiGLU the gate rows), `up` the matching up rows (unused otherwise).
+// A lane holds token lane%32 and weight rows 8g + 4*(lane/32) + 0..3.
+template <int EPI>
+__device__ __forceinline__ void epilogue_block(const floatx16& gate, const floatx16& up, bf16_t* __restrict__ c,
+                                               int row0, int row_end, int n0, int N, int wm, int wn, int mi, int ni,
+                                               int lane) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
+    const int r = row0 + wm * 128 + mi * 32 + (lane & 31);
+    if (r >= row_end) return;
+    bf16_t* crow = c + (size_t)r * N;
+    const int col0 = n0 + wn * (BNO / WN) + ni * 32 + (lane >> 5) * 4;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = col0 + 8 * g;
+        if (n >= N) continue;
+        floatx4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float t = gate[4 * g + q];
+            if (EPI == kSwiglu) t = t / (1.0f + __expf(-t)) * up[4 * g + q];
+            if (EPI == kRelu) t = fmaxf(t, 0.0f);
+            v[q] = t;
+        }
+        bf16x4 o = __builtin_convertvector(v, bf16x4);
+        *reinterpret_cast<bf16x4*>(crow + n) = o;
+    }
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c, int row0, int row_end, int n0,
+                                         int N, int wm, int wn, int lane) {
+    constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
+#pragma unroll
+    for (int mi = 0; mi < TB; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NB; ++ni)
+            epilogue_block<EPI>(acc[ni][mi], acc[EPI == kSwiglu ? ni + NB : ni][mi], c, row0, row_end, n0, N, wm, wn, mi,
+                                ni, lane);
+}
+
+template <int EPI, bool KTAIL>
+__global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
+                                                         const int32_t* __restrict__ offsets,
+                                                         const bf16_t* __restrict__ b0,
+                                                         const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
+                                                         float* __restrict__ partials, int S, int N, int K,
+                                                         int n_tiles) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
+    extern __shared__ __align__(16) char lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
+    const int k_tiles_all = (K + BK - 1) / BK;
+    const int G = gridDim.x;
+    const Plan plan = make_plan(offsets, S, n_tiles, k_tiles_all, G);
+    const int rows_total = offsets[S];
+    const int xcd = blockIdx.x % XCDS, cu = blockIdx.x / XCDS, per_xcd = G / XCDS;
+    const int sk_item = xcd * per_xcd + cu;  // this workgroup's piece of the leftover tiles
 
-    // ---- global -> LDS ---------------------------------------------------------------------
-    // Wavefront w issues, per tile and per operand, load instructions i = 0..LPW-1; instruction
-    // (w, i) fills tile rows (LPW*w + i)*16 .. +15.  Lane l lands in row l>>2, chunk position l&3
-    // and therefore fetches global chunk (l&3) ^ ((row>>2)&3).
+    // lane-constant parts of the addressing
     const int l_row = lane >> 2;
     const int l_chunk = (lane & 3) ^ ((l_row >> 2) & 3);
     const uint32_t a_bytes = (uint32_t)rows_total * (uint32_t)K * 2u;
     const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
-    uint32_t a_voff[LPW], b_voff[LPW];
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int tr = (LPW * wave + i) * 16 + l_row;  // row of the tile
-        int r = row0 + tr;
-        r = r < row_end ? r : row_end - 1;
-        a_voff[i] = ((uint32_t)r * (uint32_t)K + l_chunk * 8) * 2u;
-        int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
-        n = n < N ? n : N - 1;
-        b_voff[i] = ((uint32_t)n * (uint32_t)K + l_chunk * 8) * 2u;
-    }
-    const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // upper wavefronts load the W3 half
     const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a, a_bytes);
-    const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(wsel + (size_t)slot * N * K, b_bytes);
-    const int k_tiles = (K + BK - 1) / BK;
-    const int k_last = (k_tiles - 1) * BK;
-    // one load instruction: j < LPW token rows, j >= LPW weight rows, of the tile starting at element k0
-    auto issue_load = [&](int j, int stage, int k0) {
-        const bool tok = j < LPW;
-        const int i = tok ? j : j - LPW;
-        uint32_t voff = tok ? a_voff[i] : b_voff[i];
-        if (KTAIL && k0 + l_chunk * 8 >= K) voff = tok ? a_bytes : b_bytes;  // out of range: zeros
-        char* dst = lds + stage * STAGE_BYTES + (tok ? 0 : TILE_BYTES) + (LPW * wave + i) * 1024;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(tok ? a_rsrc : b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 0);
-    };
-
-    // ---- fragment addresses (bytes within a stage, for the first MFMA step; the second is ^32) ----
-    // SwiGLU: weight blocks 0..WB/2-1 are gate rows, WB/2..WB-1 the matching up rows
+    const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // upper wavefronts load the W3 half
     const int f_row = lane & 31;
     const int f_sw = (((lane >> 5) ^ ((f_row >> 2) & 3)) & 3) * 16;
     const int x_off = (wm * 128 + f_row) * ROW_BYTES + f_sw;  // + i * 32 rows
-    int w_off[WB];
+    int w_off[WB];  // SwiGLU: weight blocks 0..WB/2-1 are gate rows, WB/2..WB-1 the matching up rows
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
         int rr;
@@ -164,112 +214,179 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         w_off[i] = TILE_BYTES + (rr + f_row) * ROW_BYTES + f_sw;
     }
 
-    floatx16 acc[WB][TB];  // [weight block][token block]
-#pragma unroll
-    for (int i = 0; i < WB; ++i)
-#pragma unroll
-        for (int j = 0; j < TB; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    bf16x8 xf[2][TB], wf[2][WB];
-    auto load_frags = [&](int buf, int stage, int kk) {
-        const char* base = lds + stage * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < TB; ++i)
-            xf[buf][i] = *reinterpret_cast<const bf16x8*>(base + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
-#pragma unroll
-        for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(base + (w_off[i] ^ (kk * 32)));
-    };
-    auto mfma_step = [&](int buf) {
-#pragma unroll
-        for (int ni = 0; ni < WB; ++ni)
-#pragma unroll
-            for (int mi = 0; mi < TB; ++mi)
-                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
-    };
-    // the step's MFMAs with its LDS reads and global->LDS loads slotted in one at a time
-    auto interleave = [&]() {
-#pragma unroll
-        for (int i = 0; i < TB * WB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                // one MFMA
-            if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
-            else if (i < TB + WB + LOADS / 2) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
-        }
-    };
-
-    // ---- prologue: tiles 0..2 on their way, tile 0 landed ------------------------------------
-#pragma unroll
-    for (int t = 0; t < STAGES - 1; ++t) {
-        const int k0 = t * BK < k_last ? t * BK : k_last;
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) issue_load(j, t, k0);
-    }
-    barrier_keep_loads<2 * LOADS>();
-    load_frags(0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- main loop ---------------------------------------------------------------------------
-    // Near the end of K the loads are clamped to the last tile: the surplus lands in a stage that
-    // nobody reads any more, and the loop body stays free of branches.
-    for (int t = 0; t < k_tiles; ++t) {
-        const int stage = t & (STAGES - 1);
-        const int stage_in = (t + STAGES - 1) & (STAGES - 1);  // receives tile t+3; held tile t-1
-        int k3 = (t + STAGES - 1) * BK;
-        k3 = k3 < k_last ? k3 : k_last;
-        // step 0: MFMAs on the first 16 of K; second-half fragments and half of the loads issued
-        load_frags(1, stage, 1);
-#pragma unroll
-        for (int j = 0; j < LOADS / 2; ++j) issue_load(j, stage_in, k3);
-        mfma_step(0);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        // tile t+1 has landed once only tile t+2 (8 loads) and this step's 4 loads are pending; the
-        // LDS reads of tile t are complete: after the barrier its stage is dead, tile t+1 visible
-        barrier_keep_loads<LOADS + LOADS / 2>();
-        __builtin_amdgcn_sched_barrier(0);
-        // step 1: MFMAs on the second 16 of K; first fragments of tile t+1 and the other loads issued
-        load_frags(0, (t + 1) & (STAGES - 1), 0);
-#pragma unroll
-        for (int j = LOADS / 2; j < LOADS; ++j) issue_load(j, stage_in, k3);
-        mfma_step(1);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    __builtin_amdgcn_s_waitcnt(wait_imm(0));  // surplus loads must not outlive the workgroup's LDS
-
-    // ---- epilogue: lane holds, per block, token lane%32 and weight rows 8g + 4*(lane/32) + 0..3 ---
-    constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
-    const int col0 = n0 + wn * (BNO / WN) + (lane >> 5) * 4;
-#pragma unroll
-    for (int mi = 0; mi < TB; ++mi) {
-        const int r = row0 + wm * 128 + mi * 32 + (lane & 31);
-        if (r >= row_end) continue;
-        bf16_t* crow = c + (size_t)r * N;
-#pragma unroll
-        for (int ni = 0; ni < NB; ++ni) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = col0 + ni * 32 + 8 * g;
-                if (n >= N) continue;
-                floatx4 v;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float t = acc[ni][mi][4 * g + q];
-                    if (EPI == kSwiglu) t = t / (1.0f + __expf(-t)) * acc[ni + NB][mi][4 * g + q];
-                    if (EPI == kRelu) t = fmaxf(t, 0.0f);
-                    v[q] = t;
-                }
-                bf16x4 o = __builtin_convertvector(v, bf16x4);
-                *reinterpret_cast<bf16x4*>(crow + n) = o;
+    for (int item = 0; item <= plan.rounds; ++item) {
+        // ---- what to do in this trip -------------------------------------------------------------
+        int L, kb = 0, ke = k_tiles_all, piece = -1;
+        if (item < plan.rounds) {
+            L = xcd * plan.rounds * per_xcd + item * per_xcd + cu;
+        } else {
+            if (sk_item >= plan.left * plan.splits) break;
+            L = plan.rounds * G + sk_item / plan.splits;
+            if (plan.splits > 1) {
+                const int sp = sk_item % plan.splits;
+                kb = (int)((long long)k_tiles_all * sp / plan.splits);
+                ke = (int)((long long)k_tiles_all * (sp + 1) / plan.splits);
+                piece = sk_item;
             }
+        }
+        int slot, row0, row_end, nt;
+        decode_tile(offsets, S, n_tiles, L, slot, row0, row_end, nt);
+        const int n0 = nt * BNO;
+
+        // ---- global -> LDS -------------------------------------------------------------------------
+        // Wavefront w issues, per K tile and per operand, load instructions i = 0..LPW-1; instruction
+        // (w, i) fills tile rows (LPW*w + i)*16 .. +15.  Lane l lands in row l>>2, chunk position l&3
+        // and therefore fetches global chunk (l&3) ^ ((row>>2)&3).
+        uint32_t a_voff[LPW], b_voff[LPW];
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int tr = (LPW * wave + i) * 16 + l_row;  // row of the tile
+            int r = row0 + tr;
+            r = r < row_end ? r : row_end - 1;
+            a_voff[i] = ((uint32_t)r * (uint32_t)K + l_chunk * 8) * 2u;
+            int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
+            n = n < N ? n : N - 1;
+            b_voff[i] = ((uint32_t)n * (uint32_t)K + l_chunk * 8) * 2u;
+        }
+        const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(wsel + (size_t)slot * N * K, b_bytes);
+        const int k_tiles = ke - kb;
+        const int k_first = kb * BK, k_last = (ke - 1) * BK;
+        // one load instruction: j < LPW token rows, j >= LPW weight rows, of the K tile starting at element k0
+        auto issue_load = [&](int j, int stage, int k0) {
+            const bool tok = j < LPW;
+            const int i = tok ? j : j - LPW;
+            uint32_t voff = tok ? a_voff[i] : b_voff[i];
+            if (KTAIL && k0 + l_chunk * 8 >= K) voff = tok ? a_bytes : b_bytes;  // out of range: zeros
+            char* dst = lds + stage * STAGE_BYTES + (tok ? 0 : TILE_BYTES) + (LPW * wave + i) * 1024;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(tok ? a_rsrc : b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 0);
+        };
+
+        floatx16 acc[WB][TB];  // [weight block][token block]
+#pragma unroll
+        for (int i = 0; i < WB; ++i)
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+        bf16x8 xf[2][TB], wf[2][WB];
+        auto load_frags = [&](int buf, int stage, int kk) {
+            const char* base = lds + stage * STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < TB; ++i)
+                xf[buf][i] = *reinterpret_cast<const bf16x8*>(base + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
+#pragma unroll
+            for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(base + (w_off[i] ^ (kk * 32)));
+        };
+        auto mfma_step = [&](int buf) {
+#pragma unroll
+            for (int ni = 0; ni < WB; ++ni)
+#pragma unroll
+                for (int mi = 0; mi < TB; ++mi)
+                    acc[ni][mi] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
+        };
+        // the step's MFMAs with its LDS reads and global->LDS loads slotted in one at a time
+        auto interleave = [&]() {
+#pragma unroll
+            for (int i = 0; i < TB * WB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                // one MFMA
+                if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
+                else if (i < TB + WB + LOADS / 2) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
+            }
+        };
+
+        // ---- prologue: K tiles 0..2 of this piece on their way, the first landed -------------------
+        // (every wavefront is past the last barrier of the previous trip, so nobody reads LDS any more)
+#pragma unroll
+        for (int t = 0; t < STAGES - 1; ++t) {
+            const int k0 = k_first + t * BK < k_last ? k_first + t * BK : k_last;
+#pragma unroll
+            for (int j = 0; j < LOADS; ++j) issue_load(j, t, k0);
+        }
+        barrier_keep_loads<2 * LOADS>();
+        load_frags(0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- main loop -----------------------------------------------------------------------------
+        // Near the end of K the loads are clamped to the last tile: the surplus lands in a stage that
+        // nobody reads any more, and the loop body stays free of branches.
+        for (int t = 0; t < k_tiles; ++t) {
+            const int stage = t & (STAGES - 1);
+            const int stage_in = (t + STAGES - 1) & (STAGES - 1);  // receives tile t+3; held tile t-1
+            int k3 = k_first + (t + STAGES - 1) * BK;
+            k3 = k3 < k_last ? k3 : k_last;
+            // step 0: MFMAs on the first 16 of K; second-half fragments and half of the loads issued
+            load_frags(1, stage, 1);
+#pragma unroll
+            for (int j = 0; j < LOADS / 2; ++j) issue_load(j, stage_in, k3);
+            mfma_step(0);
+            interleave();
+            __builtin_amdgcn_sched_barrier(0);
+            // tile t+1 has landed once only tile t+2 (8 loads) and this step's 4 loads are pending; the
+            // LDS reads of tile t are complete: after the barrier its stage is dead, tile t+1 visible
+            barrier_keep_loads<LOADS + LOADS / 2>();
+            __builtin_amdgcn_sched_barrier(0);
+            // step 1: MFMAs on the second 16 of K; first fragments of tile t+1 and the other loads issued
+            load_frags(0, (t + 1) & (STAGES - 1), 0);
+#pragma unroll
+            for (int j = LOADS / 2; j < LOADS; ++j) issue_load(j, stage_in, k3);
+            mfma_step(1);
+            interleave();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // surplus loads must not land in the next trip's tiles (or outlive the workgroup's LDS)
+        barrier_keep_loads<0>();
+
+        if (piece < 0) {
+            epilogue<EPI>(acc, c, row0, row_end, n0, N, wm, wn, lane);
+        } else {  // a K piece of a leftover tile: raw accumulators to the workspace, [register][thread]
+            float* dst = partials + (size_t)piece * (BM * BR) + tid;
+#pragma unroll
+            for (int i = 0; i < WB; ++i)
+#pragma unroll
+                for (int j = 0; j < TB; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) dst[((i * TB + j) * 16 + v) * (64 * NW)] = acc[i][j][v];
         }
     }
 }
 
+// Adds the K pieces of each leftover tile in piece order and applies the epilogue.  One workgroup
+// per (leftover tile, 32 x 32 block position of the wavefronts), so the sum itself is spread over
+// the chip.  grid.x = kFixupUnits * (G - 1) covers every possible leftover tile; G = workgroups of
+// the main launch.
+template <int EPI>
+__global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
+                                                        const float* __restrict__ partials, int S, int N, int K,
+                                                        int n_tiles, int G) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
+    constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
+    constexpr int UNITS = TB * NB;
+    const Plan plan = make_plan(offsets, S, n_tiles, (K + BK - 1) / BK, G);
+    const int tile = blockIdx.x / UNITS, unit = blockIdx.x % UNITS;
+    if (plan.splits <= 1 || tile >= plan.left) return;
+    const int mi = unit / NB, ni = unit % NB;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int slot, row0, row_end, nt;
+    decode_tile(offsets, S, n_tiles, plan.rounds * G + tile, slot, row0, row_end, nt);
+    floatx16 gate, up;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { gate[v] = 0.0f; up[v] = 0.0f; }
+    for (int sp = 0; sp < plan.splits; ++sp) {
+        const float* src = partials + (size_t)(tile * plan.splits + sp) * (BM * BR) + tid;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            gate[v] += src[((ni * TB + mi) * 16 + v) * (64 * NW)];
+            if (EPI == kSwiglu) up[v] += src[(((ni + NB) * TB + mi) * 16 + v) * (64 * NW)];
+        }
+    }
+    epilogue_block<EPI>(gate, up, c, row0, row_end, nt * BNO, N, wave / WN, wave % WN, mi, ni, lane);
+}
+
 template <int EPI, bool KTAIL>
 hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
-                      unsigned blocks, int S, int N, int K, int n_tiles, hipStream_t st) {
+                      float* partials, int S, int N, int K, int n_tiles, hipStream_t st) {
     auto kern = grouped_gemm_bf16<EPI, KTAIL>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -278,20 +395,20 @@ hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0,
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<blocks, 64 * NW, LDS_BYTES, st>>>(a, offsets, b0, b1, c, S, N, K, n_tiles);
+    kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles);
+    constexpr int kFixupUnits = TB * (EPI == kSwiglu ? WB / 2 : WB);
+    splitk_fixup<EPI><<<kFixupUnits * (kPersistentGroups - 1), 64 * NW, 0, st>>>(offsets, c, partials, S, N, K,
+                                                                                 n_tiles, kPersistentGroups);
     return hipGetLastError();
 }
 
 template <int EPI>
-hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int A,
-                      int S, int N, int K, hipStream_t st) {
+hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
+                      float* partials, int S, int N, int K, hipStream_t st) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     const int n_tiles = (N + BNO - 1) / BNO;
-    const int m_tiles = (A + BM - 1) / BM + S;
-    long long blocks = (long long)n_tiles * m_tiles;
-    blocks = (blocks + XCDS - 1) / XCDS * XCDS;
-    if (K % BK == 0) return launch_cfg<EPI, false>(a, offsets, b0, b1, c, (unsigned)blocks, S, N, K, n_tiles, st);
-    return launch_cfg<EPI, true>(a, offsets, b0, b1, c, (unsigned)blocks, S, N, K, n_tiles, st);
+    if (K % BK == 0) return launch_cfg<EPI, false>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles, st);
+    return launch_cfg<EPI, true>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles, st);
 }
 
 }  // namespace
@@ -299,19 +416,21 @@ hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0,
 hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
                                  const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                  int passes, hipStream_t st) {
-    const int A = d.T * d.k;
-    bf16_t* h = reinterpret_cast<bf16_t*>(static_cast<uint8_t*>(ws) + ffn_ws_layout(d).h);
+    const FfnWs lay = ffn_ws_layout(d);
+    bf16_t* h = reinterpret_cast<bf16_t*>(static_cast<uint8_t*>(ws) + lay.h);
+    float* partials = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + lay.partials);
     const bf16_t* xp = static_cast<const bf16_t*>(x_perm);
     hipError_t e = hipSuccess;
     if (!(passes & 1)) {
     } else if (d.act == EMOE_ACT_SWIGLU)
-        e = launch_one<kSwiglu>(xp, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h, A,
-                                d.S, d.d_ff, d.d_model, st);
+        e = launch_one<kSwiglu>(xp, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h,
+                                partials, d.S, d.d_ff, d.d_model, st);
     else
-        e = launch_one<kRelu>(xp, offsets, static_cast<const bf16_t*>(w1), nullptr, h, A, d.S, d.d_ff, d.d_model, st);
+        e = launch_one<kRelu>(xp, offsets, static_cast<const bf16_t*>(w1), nullptr, h, partials, d.S, d.d_ff, d.d_model,
+                              st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain>(h, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm), A,
-                              d.S, d.d_model, d.d_ff, st);
+    return launch_one<kPlain>(h, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm),
+                              partials, d.S, d.d_model, d.d_ff, st);
 }
 
 }  // namespace emoe

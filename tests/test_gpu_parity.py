@@ -28,6 +28,8 @@ SMALL_CASES = [
     cfg("tiled_swiglu_ragged", T=700, d_model=328, d_ff=456, E=8, k=2, R=4, index=43),
     cfg("tiled_swiglu_aligned", T=512, d_model=512, d_ff=768, E=8, k=2, R=3, S=5, index=44),
     cfg("tiled_relu_skewed", act="relu", T=1500, d_model=256, d_ff=520, E=64, k=1, R=16, zipf_s=1.1, index=45),
+    # few output tiles and a long K: leftover tiles are split along K into pieces (with a K tail in both passes)
+    cfg("tiled_splitk_ktail", T=600, d_model=1032, d_ff=1160, E=8, k=2, R=4, S=6, index=58),
     cfg("tiled_topk6", T=600, d_model=256, d_ff=384, E=64, k=6, R=24, zipf_s=1.2, resident="popular", index=46),
     # streaming path (A <= 48 S): few rows per slot, slots with 0 rows, a slot with > 64 rows
     cfg("stream_decode", T=64, d_model=512, d_ff=1088, E=8, k=2, R=6, index=47),

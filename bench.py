@@ -19,6 +19,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+# HBM bytes per launch of the dominant kernels, from two hardware-counter runs of this command
+# (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for a 1 GiB device copy:
+# x2.00 and x1.00).  Counters cannot be read from inside the process, so the figures are carried here.
+TRAFFIC_BYTES_PREFILL_PASS1 = (2040888.5 * 2.00 + 335429.8 * 1.00) * 1024   # 4.52 GB: operands re-read through L2
+TRAFFIC_BYTES_DECODE_PASS1 = (701657.9 * 2.00 + 3665.8 * 1.00) * 1024       # 1.44 GB: 1.02x the weight bytes
 
 
 def log(msg):
@@ -84,6 +89,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = size the sample for about 15 s")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device-to-device copy, so that a hardware-counter run of this "
+                         "command also holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards by tokens with no "
@@ -97,6 +105,15 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     P.lib()  # fails loudly if libemoe.so has not been built
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read, 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     # ---------------- prefill (headline) ----------------
     c3 = gen.C3
@@ -114,9 +131,10 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C3 Mixtral-8x7B-shaped prefill layer: T=4096 d_model=4096 d_ff=14336 E=8 top-2 SwiGLU, "
                                "4 of 8 experts resident, bf16", "rows_per_slot": [int(c) for c in counts]},
-        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16<SwiGLU> (FFN pass 1)", "achieved": tf1,
+        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16<SwiGLU> + splitk_fixup (FFN pass 1)", "achieved": tf1,
                      "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": tf1 / PEAK_BF16_MFMA_TFLOPS,
-                     "traffic": None, "launch_ms": ms["ffn_pass1"]},
+                     "traffic": TRAFFIC_BYTES_PREFILL_PASS1, "traffic_unit": "bytes per launch",
+                     "launch_ms": ms["ffn_pass1"]},
         "prefill_breakdown_ms": ms,
         "prefill_layer_mfma_frac": (flop_pass1 + flop_pass2) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
         "prefill_pass2_tflops": flop_pass2 / (ms["ffn_pass2"] * 1e-3) / 1e12,
@@ -141,8 +159,9 @@ def main():
             "config": {"workload": "C4 Mixtral-8x7B-shaped decode step: 64 tokens, top-2, 6 of 8 experts resident, "
                                    "bf16; 3 rotating copies of the slot buffers", "rows_per_slot": [int(c) for c in dcounts]},
             "roofline": {"bound": "hbm", "kernel": "stream_gemm_bf16<SwiGLU> (FFN pass 1)", "achieved": gbs1,
-                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs1 / PEAK_HBM_GBS, "traffic": None,
-                         "launch_ms": dms["ffn_pass1"]},
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs1 / PEAK_HBM_GBS,
+                         "traffic": TRAFFIC_BYTES_DECODE_PASS1, "traffic_unit": "bytes per launch",
+                         "algorithmic_bytes": bytes_pass1, "launch_ms": dms["ffn_pass1"]},
             "breakdown_ms": dms,
             "pass2_gbs": bytes_pass2 / (dms["ffn_pass2"] * 1e-3) / 1e9,
             "layer_hbm_frac": (bytes_pass1 + bytes_pass2) / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,

@@ -78,7 +78,81 @@ def run_workload(torch, P, gen, cfg, steps, warmup, copies):
     wall, ms = timed_steps(torch, P, dev, buf, steps, warmup, sets)
     torch.cuda.synchronize()
     counts = buf.slot_counts.cpu().numpy()
-    return inp, wall, ms, counts
+    return inp, wall, ms, counts, dev, buf
+
+
+def layer_work(cfg, counts):
+    """Algorithmic work of one layer forward: flop of the routed rows, weight bytes of the non-empty slots."""
+    A = cfg.T * cfg.k
+    mats = 3 if cfg.act == "swiglu" else 2
+    occupied = int((counts > 0).sum())
+    return 2.0 * A * mats * cfg.d_model * cfg.d_ff, occupied * mats * cfg.d_model * cfg.d_ff * cfg.elem_bytes
+
+
+def other_config(torch, P, gen, cfg, steps, warmup, copies, label):
+    _, wall, ms, counts, dev, buf = run_workload(torch, P, gen, cfg, steps, warmup, copies)
+    del dev, buf
+    torch.cuda.empty_cache()
+    flop, wbytes = layer_work(cfg, counts)
+    t = wall / steps
+    log(f"{cfg.name}: {t * 1e3:.3f} ms/step, breakdown {ms}")
+    return {"config": {"workload": label, "rows_per_slot_max": int(counts.max()), "slots_with_rows": int((counts > 0).sum())},
+            "value": cfg.T / t, "unit": "tokens/s", "ms_per_step": t * 1e3, "steps": steps, "breakdown_ms": ms,
+            "layer_tflops": flop / t / 1e12, "layer_mfma_frac": flop / t / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+            "layer_weight_gbs": wbytes / t / 1e9, "layer_hbm_frac": wbytes / t / 1e9 / PEAK_HBM_GBS}
+
+
+def bench_load(torch, P, gen, c3, dev3, buf3):
+    """Section 4's upload: experts from pinned host memory into slots on a side stream.  Times one
+    Mixtral-sized expert, a list of four, and the list of four while the prefill layer runs on the
+    compute stream out of other slot buffers."""
+    import numpy as np
+    f, d, E = c3.d_ff, c3.d_model, c3.E
+    S = 4
+    desc = P.make_desc(c3.T, d, f, E, c3.k, S, c3.dtype, c3.act)
+    pin = lambda shape: torch.zeros(shape, dtype=torch.bfloat16).pin_memory()
+    h1 = [pin((f, d)) for _ in range(5)] + [None] * (E - 5)
+    h3 = [pin((f, d)) for _ in range(5)] + [None] * (E - 5)
+    h2 = [pin((d, f)) for _ in range(5)] + [None] * (E - 5)
+    w1 = torch.empty((S, f, d), dtype=torch.bfloat16, device="cuda")
+    w3, w2 = torch.empty_like(w1), torch.empty((S, d, f), dtype=torch.bfloat16, device="cuda")
+    soe = torch.full((E,), -1, dtype=torch.int32, device="cuda")
+    eos = torch.full((S,), -1, dtype=torch.int32, device="cuda")
+    mirror = np.full(S, -1, dtype=np.int32)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    expert_bytes = 3 * f * d * 2
+
+    def timed_load(experts, slots):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        P.emoe_load_experts(desc, experts, slots, h1, h3, h2, w1, w3, w2, soe, eos, mirror, side)
+        e1.record(side)
+        return e0, e1
+
+    timed_load([0, 1, 2, 3], [0, 1, 2, 3]); side.synchronize()          # untimed: first touch of the pinned pages
+    e0, e1 = timed_load([0, 1, 2, 3], [0, 1, 2, 3]); side.synchronize()
+    four_ms = e0.elapsed_time(e1)
+    e0, e1 = timed_load([4], [0]); side.synchronize()
+    one_ms = e0.elapsed_time(e1)
+    # overlapped with the prefill layer
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_fwd = 40
+    e0, e1 = timed_load([0, 1, 2, 3], [0, 1, 2, 3])
+    c0.record()
+    for _ in range(n_fwd):
+        P.layer_forward(buf3, dev3.x, dev3.w_gate, dev3.gate_bias, dev3.slot_of_expert, dev3.w1_slots, dev3.w3_slots,
+                        dev3.w2_slots)
+    c1.record()
+    torch.cuda.synchronize()
+    ov_ms, fwd_ms = e0.elapsed_time(e1), c0.elapsed_time(c1) / n_fwd
+    res = {"one_expert": {"bytes": expert_bytes, "ms": one_ms, "gbs": expert_bytes / one_ms / 1e6},
+           "four_experts": {"bytes": 4 * expert_bytes, "ms": four_ms, "gbs": 4 * expert_bytes / four_ms / 1e6},
+           "four_experts_during_prefill": {"ms": ov_ms, "gbs": 4 * expert_bytes / ov_ms / 1e6,
+                                           "layer_ms_per_step_meanwhile": fwd_ms},
+           "note": "pinned host -> HBM through emoe_load_experts on a side stream; not part of tokens/s"}
+    log(f"load: {res}")
+    return res
 
 
 def main():
@@ -88,6 +162,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the upload measurement and the C5 / C2 workloads")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = size the sample for about 15 s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy, so that a hardware-counter run of this "
@@ -117,7 +192,7 @@ def main():
 
     # ---------------- prefill (headline) ----------------
     c3 = gen.C3
-    inp3, wall, ms, counts = run_workload(torch, P, gen, c3, args.steps, args.warmup, copies=1)
+    inp3, wall, ms, counts, dev3, buf3 = run_workload(torch, P, gen, c3, args.steps, args.warmup, copies=1)
     ms_step = wall / args.steps * 1e3
     tokens_s = c3.T * args.steps / wall
     A = c3.T * c3.k
@@ -141,13 +216,18 @@ def main():
     }
     log(f"prefill: {ms_step:.3f} ms/step, {tokens_s:,.0f} tokens/s, pass1 {tf1:.0f} TFLOP/s, breakdown {ms}")
 
+    if not args.no_extras:
+        result["load_experts"] = bench_load(torch, P, gen, c3, dev3, buf3)
+    del inp3, dev3, buf3
+    torch.cuda.empty_cache()
+
     # ---------------- decode ----------------
     if not args.no_decode:
-        del inp3
-        torch.cuda.empty_cache()
         c4 = gen.C4
         dsteps, dwarm = max(args.steps, 30), max(args.warmup, 6)
-        _, dwall, dms, dcounts = run_workload(torch, P, gen, c4, dsteps, dwarm, copies=3)
+        _, dwall, dms, dcounts, ddev, dbuf = run_workload(torch, P, gen, c4, dsteps, dwarm, copies=3)
+        del ddev, dbuf
+        torch.cuda.empty_cache()
         el = c4.elem_bytes
         occupied = int((dcounts > 0).sum())
         bytes_pass1 = occupied * 2 * c4.d_model * c4.d_ff * el      # W1 and W3 of the non-empty slots
@@ -167,6 +247,15 @@ def main():
             "layer_hbm_frac": (bytes_pass1 + bytes_pass2) / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         }
         log(f"decode: {d_ms:.3f} ms/step, pass1 {gbs1:.0f} GB/s, breakdown {dms}")
+
+    # ---------------- the other workloads (reported, not the headline) ----------------
+    if not args.no_extras:
+        result["c5"] = other_config(torch, P, gen, gen.C5, 20, 5, 1,
+                                    "C5 fine-grained layer: T=8192 d_model=2048 d_ff=1408 E=64 top-6 SwiGLU, 24 of 64 "
+                                    "resident (the most popular), Zipf(1.2) gate bias, bf16")
+        result["c2"] = other_config(torch, P, gen, gen.C2, 40, 8, 4,
+                                    "C2 Switch-style layer: T=1024 d_model=768 d_ff=3072 E=64 top-1 ReLU, 16 of 64 resident, "
+                                    "Zipf(1.1) gate bias, bf16; 4 rotating copies of the slot buffers")
 
     # ---------------- the oracle on the host cores, on a bounded sample of the prefill workload ------------
     if not args.no_cpu_baseline:

@@ -23,7 +23,7 @@
  *     on the host before anything is enqueued; on a validation error nothing
  *     is enqueued and no output is touched.  T == 0 is a successful no-op.
  *   - Limits: 1 <= k <= S <= E <= 64; d_model and d_ff multiples of 8;
- *     T*k < 2^31 / max(d_model, d_ff).
+ *     (T*k + 2) * max(d_model, d_ff) <= 2^31.
  */
 #ifndef EMOE_H
 #define EMOE_H

@@ -21,7 +21,9 @@ int validate_desc(const emoe_layer_desc* d) {
     if (d->d_model % 8 != 0 || d->d_ff % 8 != 0) return EMOE_ERR_UNSUPPORTED;
     const long long A = (long long)d->T * d->k;
     const long long widest = d->d_model > d->d_ff ? d->d_model : d->d_ff;
-    if (A * widest >= (1ll << 31)) return EMOE_ERR_SHAPE;
+    // 32-bit byte offsets into the activation buffers, with room for one more row past the end (the
+    // kernels address "out of range" as buffer size + an offset within a row)
+    if ((A + 2) * widest > (1ll << 31)) return EMOE_ERR_SHAPE;
     return EMOE_OK;
 }
 

@@ -51,6 +51,9 @@ int validate_desc(const emoe_layer_desc* d);
 
 // `passes` of the FFN launchers: bit 0 = pass 1 (x_perm -> h), bit 1 = pass 2 (h -> y_perm).
 // Kernel launchers (each returns a hipError_t converted to emoe_status by the caller).
+hipError_t launch_route_bf16(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
+                             const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                             hipStream_t st);
 hipError_t launch_route(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
                         const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st);
 hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t* topk_expert,

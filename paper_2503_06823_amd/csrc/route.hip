@@ -1,5 +1,6 @@
 // Gate logits and resident-restricted top-k (eMoE Section 1: the gate; Section 3.2.2, last
-// paragraph: a token whose expert is not on the GPU goes to its next-best expert that is).
+// paragraph: a token whose expert is not on the GPU goes to its next-best expert that is),
+// fp32 inputs.  bf16 inputs take the matrix-core kernel of route_mfma.hip.
 //
 // One wavefront (or, when there are few tokens, four) owns one token at a time.  Its 64 lanes
 // split the d_model axis (16 bytes per lane per step, so a step reads 1 KiB of the token row
@@ -14,18 +15,6 @@ namespace emoe {
 namespace {
 
 template <typename T> struct Vec;
-template <> struct Vec<bf16_t> {
-    static constexpr int N = 8;
-    __device__ static void load(const bf16_t* p, float (&v)[8]) {
-        uint4 r = *reinterpret_cast<const uint4*>(p);
-        uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-};
 template <> struct Vec<float> {
     static constexpr int N = 4;
     __device__ static void load(const float* p, float (&v)[4]) {
@@ -200,7 +189,7 @@ hipError_t launch_t(const emoe_layer_desc& d, const void* x, const void* w_gate,
 hipError_t launch_route(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
                         const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st) {
     if (d.dtype == EMOE_F32) return launch_t<float>(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, st);
-    return launch_t<bf16_t>(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, st);
+    return launch_route_bf16(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, st);
 }
 
 }  // namespace emoe

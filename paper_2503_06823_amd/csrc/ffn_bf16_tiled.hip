@@ -7,7 +7,8 @@
 //
 // Tile: a workgroup of NW = 4 wavefronts (2 x 2, one per SIMD) owns 256 tokens x 256 weight rows;
 // each wavefront accumulates 128 x 128 as 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 in fp32 (256
-// accumulator registers).  Eight wavefronts (128 x 64 each) measured slower: more LDS reads per MFMA.  In the SwiGLU pass the 256 weight rows are 128 rows of W1 and the SAME 128 rows of
+// accumulator registers).  Eight wavefronts (128 x 64 each) measured slower: more LDS reads per
+// MFMA.  In the SwiGLU pass the 256 weight rows are 128 rows of W1 and the SAME 128 rows of
 // W3, arranged so that a lane holds the gate and the up value of the same output element and the
 // activation is applied in registers.  The weight rows go on the MFMA's row operand: a lane then
 // owns four consecutive output columns of one token and stores them as one 8-byte write.
@@ -26,11 +27,12 @@
 // of tile t+3 are slotted one by one between the MFMAs, so no memory instruction waits in a full
 // queue while the matrix pipe idles.  One barrier per tile, placed between the two steps.
 //
-// Ragged groups: group sizes live on the device.  The launch covers an upper bound of M-tiles
-// (ceil(A/256) + S); every workgroup finds its (slot, m-tile, n-tile) from slot_offsets and
-// surplus workgroups exit.  Workgroup ids are dealt round-robin to the 8 XCDs, so ids are
-// remapped: each XCD walks a contiguous range of the (slot, n-tile, m-tile) order with the
-// m-tile fastest, which keeps one weight panel (and the slot's token panels) in that XCD's L2.
+// Ragged groups: group sizes live on the device.  The launch is persistent (one workgroup per CU);
+// every workgroup derives the list of (slot, m-tile, n-tile) tiles from slot_offsets and takes its
+// share (see "work distribution" below).  Workgroup ids are dealt round-robin to the 8 XCDs, so
+// ids are remapped: the workgroups of an XCD hold consecutive tiles of the (slot, n-tile, m-tile)
+// order with the m-tile fastest, which keeps one weight panel (and the slot's token panels) in
+// that XCD's L2.
 #include "common.h"
 
 namespace emoe {

@@ -85,6 +85,20 @@ int emoe_route(const emoe_layer_desc *desc, const void *x, const void *w_gate, c
                const int32_t *slot_of_expert, int32_t *topk_expert, float *topk_weight, void *stream);
 
 /*
+ * emoe_route that also observes the experts' workload (Section 3.2.2: experts
+ * are loaded "prioritizing those with the higher workload", the number of tokens
+ * an expert receives).  Outputs as emoe_route; in addition, for every token,
+ * expert_tokens[e] += 1 for each of the k experts the token would use if every
+ * expert were resident (the k largest logits over all E experts, same tie rule).
+ * expert_tokens [E] int64 dev, in/out: counts accumulate across calls (a layer
+ * observes many batches between two loads); the caller zeroes it.  Integer
+ * atomic adds, so the totals do not depend on execution order.
+ */
+int emoe_route_observe(const emoe_layer_desc *desc, const void *x, const void *w_gate, const float *gate_bias,
+                       const int32_t *slot_of_expert, int32_t *topk_expert, float *topk_weight,
+                       int64_t *expert_tokens, void *stream);
+
+/*
  * Token permutation into per-slot groups (the per-expert token count is the
  * "workload" of Section 3.2.2).  Stable counting sort of the assignments
  * a = 0..A-1 by key slot_of_expert[topk_expert[a]]:
@@ -167,6 +181,38 @@ int emoe_load_experts(const emoe_layer_desc *desc, int32_t n, const int32_t *exp
                       void *w1_slots, void *w3_slots, void *w2_slots, int32_t *slot_of_expert,
                       int32_t *expert_of_slot, int32_t *expert_of_slot_host, void *side_stream, void *wait_event,
                       void *done_event);
+
+/*
+ * Choice of the resident experts of one layer (Section 3.4).  Host-only helpers:
+ * every pointer is host memory, nothing is enqueued, no GPU is needed.
+ *
+ * emoe_expected_tokens: Eq. 2.  For every task type t,
+ *   N_i = (sum of W_j over the running requests j of type t + T_t * W_o[t]) * s[t] * f[t,i],
+ * T_t = number of running requests of type t; expected[i] = sum over t of N_i,
+ * accumulated in ascending t in double precision.
+ *   freq [n_tasks,E] predicted routing frequencies f, request_task [n_requests]
+ *   (0..n_tasks-1), request_tokens [n_requests] = W_j >= 0, w_out [n_tasks] = W_o,
+ *   sensitive [n_tasks] = s (0 or nonzero), expected [E] out.
+ *
+ * emoe_select_experts: the L experts with the largest expected[], in descending
+ * order (equal values: lower index first) -> selected [L].  1 <= L <= E.
+ *
+ * emoe_plan_load: Section 3.2.2, last paragraph.  Compares the selection with the
+ * residents (expert_of_slot_host [S], -1 = empty) and writes the list that
+ * emoe_load_experts takes: selected experts that are not resident, in the order
+ * of `selected` (higher workload first), each into the lowest slot that is empty
+ * or holds an unselected expert; then an entry (-1, slot) for every slot still
+ * holding an unselected expert.  Resident selected experts are not moved.
+ * expert_ids, slot_ids: out, capacity S; *n = entries written (0 = nothing to
+ * do).  The map is not modified (emoe_load_experts does that).
+ * EMOE_ERR_RESIDENT: L > S, L < k, an id out of range or repeated.
+ */
+int emoe_expected_tokens(int32_t E, int32_t n_tasks, const double *freq, int32_t n_requests,
+                         const int32_t *request_task, const int64_t *request_tokens, const double *w_out,
+                         const int32_t *sensitive, double *expected);
+int emoe_select_experts(int32_t E, const double *expected, int32_t L, int32_t *selected);
+int emoe_plan_load(int32_t E, int32_t S, int32_t k, const int32_t *expert_of_slot_host, int32_t L,
+                   const int32_t *selected, int32_t *expert_ids, int32_t *slot_ids, int32_t *n);
 
 #ifdef __cplusplus
 }

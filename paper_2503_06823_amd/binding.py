@@ -22,8 +22,9 @@ EMOE_ACT_SWIGLU, EMOE_ACT_RELU = 0, 1
 DTYPES = {"f32": EMOE_F32, "bf16": EMOE_BF16}
 ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
 
-EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_permute", "emoe_expert_ffn",
-           "emoe_expert_ffn_pass", "emoe_combine", "emoe_load_experts")
+EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_route_observe", "emoe_permute",
+           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_combine", "emoe_load_experts", "emoe_expected_tokens",
+           "emoe_select_experts", "emoe_plan_load")
 
 
 class EmoeLayerDesc(ctypes.Structure):
@@ -123,6 +124,14 @@ def emoe_route(desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_wei
     return _check(rc, "emoe_route", check)
 
 
+def emoe_route_observe(desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_weight, expert_tokens,
+                       stream=None, check=True) -> int:
+    """`expert_tokens`: int64 device tensor [E], accumulated."""
+    rc = lib().emoe_route_observe(ctypes.byref(desc), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(slot_of_expert),
+                                  _ptr(topk_expert), _ptr(topk_weight), _ptr(expert_tokens), _stream(stream))
+    return _check(rc, "emoe_route_observe", check)
+
+
 def emoe_permute(desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm, x_perm, ws,
                  ws_bytes, stream=None, check=True) -> int:
     rc = lib().emoe_permute(ctypes.byref(desc), _ptr(x), _ptr(topk_expert), _ptr(slot_of_expert), _ptr(slot_counts),
@@ -180,3 +189,43 @@ def emoe_load_experts(desc, expert_ids, slot_ids, host_w1, host_w3, host_w2, w1_
                                  _ptr(expert_of_slot), _ptr(expert_of_slot_host), _stream(side_stream),
                                  _event(wait_event), _event(done_event))
     return _check(rc, "emoe_load_experts", check)
+
+
+def _host_array(ctype, values):
+    values = list(values)
+    return (ctype * max(len(values), 1))(*values), len(values)
+
+
+def emoe_expected_tokens(freq, request_task, request_tokens, w_out, sensitive, check=True):
+    """Eq. 2 on the host.  `freq`: n_tasks rows of E frequencies.  Returns the list of E totals (or the status)."""
+    rows = [list(map(float, r)) for r in freq]
+    n_tasks, E = len(rows), len(rows[0]) if rows else 0
+    f, _ = _host_array(ctypes.c_double, [v for r in rows for v in r])
+    rt, n_req = _host_array(ctypes.c_int32, [int(v) for v in request_task])
+    rk, _ = _host_array(ctypes.c_int64, [int(v) for v in request_tokens])
+    wo, _ = _host_array(ctypes.c_double, [float(v) for v in w_out])
+    se, _ = _host_array(ctypes.c_int32, [int(v) for v in sensitive])
+    out = (ctypes.c_double * max(E, 1))()
+    rc = lib().emoe_expected_tokens(E, n_tasks, f, n_req, rt, rk, wo, se, out)
+    _check(rc, "emoe_expected_tokens", check)
+    return list(out)[:E] if rc == EMOE_OK else rc
+
+
+def emoe_select_experts(expected, L, check=True):
+    """The L experts with the largest expected token counts, descending.  Returns a list (or the status)."""
+    e, E = _host_array(ctypes.c_double, [float(v) for v in expected])
+    out = (ctypes.c_int32 * max(int(L), 1))()
+    rc = lib().emoe_select_experts(E, e, int(L), out)
+    _check(rc, "emoe_select_experts", check)
+    return list(out)[:int(L)] if rc == EMOE_OK else rc
+
+
+def emoe_plan_load(E, S, k, expert_of_slot_host, selected, check=True):
+    """The (expert_ids, slot_ids) list for emoe_load_experts (or the status)."""
+    eos, _ = _host_array(ctypes.c_int32, [int(v) for v in expert_of_slot_host])
+    sel, L = _host_array(ctypes.c_int32, [int(v) for v in selected])
+    ids, slots = (ctypes.c_int32 * max(int(S), 1))(), (ctypes.c_int32 * max(int(S), 1))()
+    n = ctypes.c_int32(0)
+    rc = lib().emoe_plan_load(int(E), int(S), int(k), eos, L, sel, ids, slots, ctypes.byref(n))
+    _check(rc, "emoe_plan_load", check)
+    return (list(ids)[:n.value], list(slots)[:n.value]) if rc == EMOE_OK else rc

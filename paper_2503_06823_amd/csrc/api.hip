@@ -89,7 +89,20 @@ int emoe_route(const emoe_layer_desc* desc, const void* x, const void* w_gate, c
     if (rc != EMOE_OK) return rc;
     if (!x || !w_gate || !slot_of_expert || !topk_expert || !topk_weight) return EMOE_ERR_NULL;
     if (desc->T == 0) return EMOE_OK;
+    hipError_t e = launch_route(*desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_weight, nullptr,
+                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}
+
+int emoe_route_observe(const emoe_layer_desc* desc, const void* x, const void* w_gate, const float* gate_bias,
+                       const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                       int64_t* expert_tokens, void* stream) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!x || !w_gate || !slot_of_expert || !topk_expert || !topk_weight || !expert_tokens) return EMOE_ERR_NULL;
+    if (desc->T == 0) return EMOE_OK;
     hipError_t e = launch_route(*desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_weight,
+                                reinterpret_cast<unsigned long long*>(expert_tokens),
                                 static_cast<hipStream_t>(stream));
     return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
 }

@@ -53,9 +53,11 @@ int validate_desc(const emoe_layer_desc* d);
 // Kernel launchers (each returns a hipError_t converted to emoe_status by the caller).
 hipError_t launch_route_bf16(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
                              const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
-                             hipStream_t st);
+                             unsigned long long* expert_tokens, hipStream_t st);
+// expert_tokens: nullptr, or [E] counters that receive each token's k experts under ordinary routing
 hipError_t launch_route(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
-                        const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st);
+                        const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                        unsigned long long* expert_tokens, hipStream_t st);
 hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t* topk_expert,
                           const int32_t* slot_of_expert, int32_t* counts, int32_t* offsets, int32_t* perm,
                           int32_t* inv_perm, void* x_perm, void* ws, hipStream_t st);

@@ -32,7 +32,9 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
                                                     const float* __restrict__ bias,
                                                     const int32_t* __restrict__ slot_of_expert,
                                                     int32_t* __restrict__ topk_expert,
-                                                    float* __restrict__ topk_weight, int T_, int d, int E, int k) {
+                                                    float* __restrict__ topk_weight,
+                                                    unsigned long long* __restrict__ expert_tokens, int T_, int d,
+                                                    int E, int k) {
     constexpr int VN = Vec<T>::N;
     __shared__ float partial[SPLIT > 1 ? 4 * 64 : 1];
     const int lane = threadIdx.x & 63;
@@ -151,45 +153,70 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
             topk_expert[(size_t)t * k + lane] = sel_e;
             topk_weight[(size_t)t * k + lane] = p / sum;
         }
+        // Workload (Section 3.2.2: the number of tokens an expert receives): the same k rounds over
+        // all E experts, resident or not.  Integer counts: the accumulated result has no order.
+        if (expert_tokens != nullptr) {
+            bool left = my_e < E;
+            int obs_e = -1;
+            for (int j = 0; j < k; ++j) {
+                float bv = logit;
+                int be = my_e;
+                bool bo = left;
+#pragma unroll
+                for (int m = 32; m >= 1; m >>= 1) {
+                    float ov = __shfl_xor(bv, m);
+                    int oe = __shfl_xor(be, m);
+                    bool oo = __shfl_xor((int)bo, m) != 0;
+                    bool take = oo && (!bo || ov > bv || (ov == bv && oe < be));
+                    if (take) { bv = ov; be = oe; bo = true; }
+                }
+                if (bo && my_e == be) left = false;
+                if (lane == j) obs_e = bo ? be : -1;
+            }
+            if (lane < k && obs_e >= 0) atomicAdd(&expert_tokens[obs_e], 1ull);
+        }
     }
 }
 
 template <typename T, int EP>
 hipError_t launch_ep(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
-                     const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st) {
+                     const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                     unsigned long long* expert_tokens, hipStream_t st) {
     const T* xp = static_cast<const T*>(x);
     const T* wg = static_cast<const T*>(w_gate);
     if (d.T <= 2048) {  // fewer than two wavefronts per SIMD otherwise: share each token among four
         int blocks = d.T < 256 * 16 ? d.T : 256 * 16;
-        route_kernel<T, EP, 4><<<blocks, 256, 0, st>>>(xp, wg, bias, slot_of_expert, topk_expert, topk_weight, d.T,
-                                                       d.d_model, d.E, d.k);
+        route_kernel<T, EP, 4><<<blocks, 256, 0, st>>>(xp, wg, bias, slot_of_expert, topk_expert, topk_weight,
+                                                       expert_tokens, d.T, d.d_model, d.E, d.k);
     } else {
         int blocks = (d.T + 3) / 4;
         if (blocks > 256 * 16) blocks = 256 * 16;
-        route_kernel<T, EP, 1><<<blocks, 256, 0, st>>>(xp, wg, bias, slot_of_expert, topk_expert, topk_weight, d.T,
-                                                       d.d_model, d.E, d.k);
+        route_kernel<T, EP, 1><<<blocks, 256, 0, st>>>(xp, wg, bias, slot_of_expert, topk_expert, topk_weight,
+                                                       expert_tokens, d.T, d.d_model, d.E, d.k);
     }
     return hipGetLastError();
 }
 
 template <typename T>
 hipError_t launch_t(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
-                    const int32_t* soe, int32_t* te, float* tw, hipStream_t st) {
-    if (d.E <= 1) return launch_ep<T, 1>(d, x, w_gate, bias, soe, te, tw, st);
-    if (d.E <= 2) return launch_ep<T, 2>(d, x, w_gate, bias, soe, te, tw, st);
-    if (d.E <= 4) return launch_ep<T, 4>(d, x, w_gate, bias, soe, te, tw, st);
-    if (d.E <= 8) return launch_ep<T, 8>(d, x, w_gate, bias, soe, te, tw, st);
-    if (d.E <= 16) return launch_ep<T, 16>(d, x, w_gate, bias, soe, te, tw, st);
-    if (d.E <= 32) return launch_ep<T, 32>(d, x, w_gate, bias, soe, te, tw, st);
-    return launch_ep<T, 64>(d, x, w_gate, bias, soe, te, tw, st);
+                    const int32_t* soe, int32_t* te, float* tw, unsigned long long* et, hipStream_t st) {
+    if (d.E <= 1) return launch_ep<T, 1>(d, x, w_gate, bias, soe, te, tw, et, st);
+    if (d.E <= 2) return launch_ep<T, 2>(d, x, w_gate, bias, soe, te, tw, et, st);
+    if (d.E <= 4) return launch_ep<T, 4>(d, x, w_gate, bias, soe, te, tw, et, st);
+    if (d.E <= 8) return launch_ep<T, 8>(d, x, w_gate, bias, soe, te, tw, et, st);
+    if (d.E <= 16) return launch_ep<T, 16>(d, x, w_gate, bias, soe, te, tw, et, st);
+    if (d.E <= 32) return launch_ep<T, 32>(d, x, w_gate, bias, soe, te, tw, et, st);
+    return launch_ep<T, 64>(d, x, w_gate, bias, soe, te, tw, et, st);
 }
 
 }  // namespace
 
 hipError_t launch_route(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
-                        const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st) {
-    if (d.dtype == EMOE_F32) return launch_t<float>(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, st);
-    return launch_route_bf16(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, st);
+                        const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                        unsigned long long* expert_tokens, hipStream_t st) {
+    if (d.dtype == EMOE_F32)
+        return launch_t<float>(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
+    return launch_route_bf16(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
 }
 
 }  // namespace emoe

@@ -60,7 +60,9 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const bf16_t* __restric
                                                          const float* __restrict__ bias,
                                                          const int32_t* __restrict__ slot_of_expert,
                                                          int32_t* __restrict__ topk_expert,
-                                                         float* __restrict__ topk_weight, int T_, int K, int E, int k) {
+                                                         float* __restrict__ topk_weight,
+                                                         unsigned long long* __restrict__ expert_tokens, int T_,
+                                                         int K, int E, int k) {
     constexpr int NB = WR == 64 ? 2 : 1;             // MFMA row blocks
     constexpr int W_BYTES = WR * ROW_BYTES;
     constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
@@ -71,12 +73,14 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const bf16_t* __restric
     extern __shared__ __align__(16) char lds[];
     float* s_bias = reinterpret_cast<float*>(lds + STAGES * STAGE_BYTES);
     int* s_resident = reinterpret_cast<int*>(s_bias + kMaxExperts);
+    int* s_hist = s_resident + kMaxExperts;  // this workgroup's tokens per expert under ordinary routing
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (threadIdx.x < kMaxExperts) {
         const int e = threadIdx.x;
         s_bias[e] = (bias != nullptr && e < E) ? bias[e] : 0.0f;
         s_resident[e] = (e < E && slot_of_expert[e] >= 0) ? 1 : 0;
+        s_hist[e] = 0;
     }
     const int t0 = blockIdx.x * TOK;
 
@@ -191,12 +195,13 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const bf16_t* __restric
     }
     const int t = t0 + c;
     const bool live = t < T_;
-    uint32_t avail = 0;
+    uint32_t avail = 0, exists = 0;
 #pragma unroll
     for (int i = 0; i < NB * 16; ++i) {
         const int e = 32 * (i >> 4) + 8 * ((i >> 2) & 3) + 4 * h + (i & 3);
         logit[i] += s_bias[e];
         if (s_resident[e]) avail |= 1u << i;
+        if (e < E) exists |= 1u << i;
     }
 
     constexpr int kNone = 0x7fffffff;
@@ -232,6 +237,33 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const bf16_t* __restric
     if (live && h == 0) {
         for (int j = 0; j < k; ++j) topk_weight[out0 + j] = topk_weight[out0 + j] / sum;
     }
+
+    // Workload (Section 3.2.2: the number of tokens an expert receives): the same k rounds over all
+    // E experts, resident or not; integer counts, so the accumulated result does not depend on order.
+    if (expert_tokens == nullptr) return;
+    for (int j = 0; j < k; ++j) {
+        float bv = 0.0f;
+        int bi = -1;
+#pragma unroll
+        for (int i = 0; i < NB * 16; ++i) {
+            const bool ok = (exists >> i) & 1u;
+            if (ok && (bi < 0 || logit[i] > bv)) { bv = logit[i]; bi = i; }
+        }
+        const int be = bi < 0 ? kNone : 32 * (bi >> 4) + 8 * ((bi >> 2) & 3) + 4 * h + (bi & 3);
+        const float ov = __shfl_xor(bv, 32);
+        const int oe = __shfl_xor(be, 32);
+        const bool mine = be != kNone && (oe == kNone || bv > ov || (bv == ov && be < oe));
+        const int win_e = mine ? be : oe;
+        if (mine) exists &= ~(1u << bi);
+        if (live && h == 0 && win_e != kNone) atomicAdd(&s_hist[win_e], 1);
+    }
+    // one wavefront: its LDS operations complete in program order
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    if (lane < E) {
+        const int n = s_hist[lane];
+        if (n > 0) atomicAdd(&expert_tokens[lane], (unsigned long long)n);
+    }
 }
 
 }  // namespace
@@ -240,8 +272,9 @@ namespace {
 
 template <int WR, int STAGES, bool KTAIL>
 hipError_t launch_cfg(const emoe_layer_desc& d, const bf16_t* x, const bf16_t* wg, const float* bias,
-                      const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st) {
-    constexpr int kLds = STAGES * (WR * ROW_BYTES + X_BYTES) + kMaxExperts * 8;
+                      const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                      unsigned long long* expert_tokens, hipStream_t st) {
+    constexpr int kLds = STAGES * (WR * ROW_BYTES + X_BYTES) + kMaxExperts * 12;
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     auto kern = route_mfma_kernel<WR, STAGES, KTAIL>;
     static bool attr_set = false;
@@ -251,30 +284,31 @@ hipError_t launch_cfg(const emoe_layer_desc& d, const bf16_t* x, const bf16_t* w
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<(d.T + TOK - 1) / TOK, 256, kLds, st>>>(x, wg, bias, slot_of_expert, topk_expert, topk_weight, d.T,
+    kern<<<(d.T + TOK - 1) / TOK, 256, kLds, st>>>(x, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, d.T,
                                                   d.d_model, d.E, d.k);
     return hipGetLastError();
 }
 
 template <int WR, int STAGES>
 hipError_t launch_wr(const emoe_layer_desc& d, const bf16_t* x, const bf16_t* wg, const float* bias,
-                     const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight, hipStream_t st) {
+                     const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
+                      unsigned long long* expert_tokens, hipStream_t st) {
     if (d.d_model % BK == 0)
-        return launch_cfg<WR, STAGES, false>(d, x, wg, bias, slot_of_expert, topk_expert, topk_weight, st);
-    return launch_cfg<WR, STAGES, true>(d, x, wg, bias, slot_of_expert, topk_expert, topk_weight, st);
+        return launch_cfg<WR, STAGES, false>(d, x, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
+    return launch_cfg<WR, STAGES, true>(d, x, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
 }
 
 }  // namespace
 
 hipError_t launch_route_bf16(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
                              const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
-                             hipStream_t st) {
+                             unsigned long long* expert_tokens, hipStream_t st) {
     const bf16_t* xp = static_cast<const bf16_t*>(x);
     const bf16_t* wg = static_cast<const bf16_t*>(w_gate);
     // as many stages as LDS holds (12 / 16 / 24 KiB each), within the 63 loads vmcnt can count
-    if (d.E <= 16) return launch_wr<16, 13>(d, xp, wg, bias, slot_of_expert, topk_expert, topk_weight, st);
-    if (d.E <= 32) return launch_wr<32, 9>(d, xp, wg, bias, slot_of_expert, topk_expert, topk_weight, st);
-    return launch_wr<64, 6>(d, xp, wg, bias, slot_of_expert, topk_expert, topk_weight, st);
+    if (d.E <= 16) return launch_wr<16, 13>(d, xp, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
+    if (d.E <= 32) return launch_wr<32, 9>(d, xp, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
+    return launch_wr<64, 6>(d, xp, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
 }
 
 }  // namespace emoe

@@ -61,6 +61,7 @@ def test_bad_descriptors_are_rejected_by_every_entry_point(kw, code):
     p = 4096  # a non-NULL address that must never be dereferenced
     assert P.emoe_workspace_bytes(d, check=False) == (code, code)
     assert P.emoe_route(d, p, p, None, p, p, p, stream=0, check=False) == code
+    assert P.emoe_route_observe(d, p, p, None, p, p, p, p, stream=0, check=False) == code
     assert P.emoe_permute(d, p, p, p, p, p, p, p, p, p, 1 << 30, stream=0, check=False) == code
     assert P.emoe_expert_ffn(d, p, p, p, p, p, p, p, 1 << 30, stream=0, check=False) == code
     assert P.emoe_combine(d, p, p, p, p, stream=0, check=False) == code
@@ -74,6 +75,7 @@ def test_null_pointers_and_small_workspace():
     assert P.lib().emoe_workspace_bytes(None, None, None) == P.EMOE_ERR_NULL
     assert P.emoe_route(d, None, p, None, p, p, p, stream=0, check=False) == P.EMOE_ERR_NULL
     assert P.emoe_route(d, p, p, None, p, p, None, stream=0, check=False) == P.EMOE_ERR_NULL
+    assert P.emoe_route_observe(d, p, p, None, p, p, p, None, stream=0, check=False) == P.EMOE_ERR_NULL
     assert P.emoe_permute(d, p, p, p, p, p, p, None, p, p, pws, stream=0, check=False) == P.EMOE_ERR_NULL
     assert P.emoe_permute(d, p, p, p, p, p, p, p, p, p, pws - 1, stream=0, check=False) == P.EMOE_ERR_WORKSPACE
     assert P.emoe_permute(d, p, p, p, p, p, p, p, p, None, pws, stream=0, check=False) == P.EMOE_ERR_WORKSPACE

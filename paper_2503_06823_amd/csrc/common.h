@@ -38,7 +38,8 @@ struct FfnWs {
     size_t partials;  // fp32 K pieces of leftover tiles (tiled bf16 path only, else 0 bytes)
     size_t total;
 };
-constexpr size_t kTiledPartialBytes = (size_t)256 * 256 * 256 * sizeof(float);  // 256 pieces of a 256x256 tile
+constexpr size_t kTiledPlanBytes = 256;  // the tiled kernel leaves its work plan here for the fix-up kernel
+constexpr size_t kTiledPartialBytes = kTiledPlanBytes + (size_t)256 * 256 * 256 * sizeof(float);  // + 256 pieces of a 256x256 tile
 constexpr int kPermuteChunk = 1024;  // assignments per workgroup in the counting sort
 PermuteWs permute_ws_layout(const emoe_layer_desc& d);
 FfnWs ffn_ws_layout(const emoe_layer_desc& d);

@@ -55,6 +55,8 @@ constexpr size_t LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KiB
 constexpr int XCDS = 8;
 constexpr int kPersistentGroups = 256;  // one workgroup per CU
 constexpr int kMaxSplits = 8;           // K pieces per leftover tile, at most
+constexpr int kFixupGroups = 255 * 16;  // workgroups of the fix-up launch: the most units there can be
+constexpr int kPlanFloats = kTiledPlanBytes / 4;  // the plan sits ahead of the partial sums
 constexpr int NW = 4;            // wavefronts per workgroup, arranged 2 (tokens) x NW/2 (weight rows)
 constexpr int WN = NW / 2;
 constexpr int TB = 4;            // 32-token blocks per wavefront (128 tokens)
@@ -191,6 +193,8 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
     const int k_tiles_all = (K + BK - 1) / BK;
     const int G = gridDim.x;
     const Plan plan = make_plan(offsets, S, n_tiles, k_tiles_all, G);
+    if (blockIdx.x == 0 && tid == 0)  // for the fix-up kernel, which then need not derive it again
+        *reinterpret_cast<int4*>(partials) = make_int4(plan.tiles, plan.rounds, plan.left, plan.splits);
     const int rows_total = offsets[S];
     const int xcd = blockIdx.x % XCDS, cu = blockIdx.x / XCDS, per_xcd = G / XCDS;
     const int sk_item = xcd * per_xcd + cu;  // this workgroup's piece of the leftover tiles
@@ -343,7 +347,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         if (piece < 0) {
             epilogue<EPI>(acc, c, row0, row_end, n0, N, wm, wn, lane);
         } else {  // a K piece of a leftover tile: raw accumulators to the workspace, [register][thread]
-            float* dst = partials + (size_t)piece * (BM * BR) + tid;
+            float* dst = partials + kPlanFloats + (size_t)piece * (BM * BR) + tid;
 #pragma unroll
             for (int i = 0; i < WB; ++i)
 #pragma unroll
@@ -354,22 +358,27 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
     }
 }
 
-// Adds the K pieces of each leftover tile in piece order and applies the epilogue.  One workgroup
+// Adds the K pieces of each leftover tile in piece order and applies the epilogue.  One unit of work
 // per (leftover tile, 32 x 32 block position of the wavefronts), so the sum itself is spread over
-// the chip.  grid.x = kFixupUnits * (G - 1) covers every possible leftover tile; G = workgroups of
-// the main launch.
+// the chip.  The plan (how many leftover tiles, how many pieces)
+// is read from the head of the workspace, where the main kernel left it: when nothing was split,
+// which the host cannot know, every workgroup exits after one load.
 template <int EPI>
 __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
+                                                        const int* __restrict__ hdr,
                                                         const float* __restrict__ partials, int S, int N, int K,
                                                         int n_tiles, int G) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
     constexpr int UNITS = TB * NB;
-    const Plan plan = make_plan(offsets, S, n_tiles, (K + BK - 1) / BK, G);
-    const int tile = blockIdx.x / UNITS, unit = blockIdx.x % UNITS;
-    if (plan.splits <= 1 || tile >= plan.left) return;
-    const int mi = unit / NB, ni = unit % NB;
+    Plan plan;  // uniform address: scalar loads
+    plan.tiles = hdr[0]; plan.rounds = hdr[1]; plan.left = hdr[2]; plan.splits = hdr[3];
+    if (plan.splits <= 1) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int u = blockIdx.x;  // the launch covers the most units there can be
+    if (u >= plan.left * UNITS) return;
+    const int tile = u / UNITS, unit = u % UNITS;
+    const int mi = unit / NB, ni = unit % NB;
     int slot, row0, row_end, nt;
     decode_tile(offsets, S, n_tiles, plan.rounds * G + tile, slot, row0, row_end, nt);
     floatx16 gate, up;
@@ -377,10 +386,17 @@ __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restric
     for (int v = 0; v < 16; ++v) { gate[v] = 0.0f; up[v] = 0.0f; }
     for (int sp = 0; sp < plan.splits; ++sp) {
         const float* src = partials + (size_t)(tile * plan.splits + sp) * (BM * BR) + tid;
+        float g[16], w[16];  // all loads of a piece in flight together, then the adds
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            gate[v] += src[((ni * TB + mi) * 16 + v) * (64 * NW)];
-            if (EPI == kSwiglu) up[v] += src[(((ni + NB) * TB + mi) * 16 + v) * (64 * NW)];
+            g[v] = src[((ni * TB + mi) * 16 + v) * (64 * NW)];
+            w[v] = EPI == kSwiglu ? src[(((ni + NB) * TB + mi) * 16 + v) * (64 * NW)] : 0.0f;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            gate[v] += g[v];
+            up[v] += w[v];
         }
     }
     epilogue_block<EPI>(gate, up, c, row0, row_end, nt * BNO, N, wave / WN, wave % WN, mi, ni, lane);
@@ -398,9 +414,8 @@ hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0,
         attr_set = true;
     }
     kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles);
-    constexpr int kFixupUnits = TB * (EPI == kSwiglu ? WB / 2 : WB);
-    splitk_fixup<EPI><<<kFixupUnits * (kPersistentGroups - 1), 64 * NW, 0, st>>>(offsets, c, partials, S, N, K,
-                                                                                 n_tiles, kPersistentGroups);
+    splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, reinterpret_cast<const int*>(partials),
+                                                        partials + kPlanFloats, S, N, K, n_tiles, kPersistentGroups);
     return hipGetLastError();
 }
 

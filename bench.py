@@ -110,10 +110,13 @@ def bench_load(torch, P, gen, c3, dev3, buf3):
     f, d, E = c3.d_ff, c3.d_model, c3.E
     S = 4
     desc = P.make_desc(c3.T, d, f, E, c3.k, S, c3.dtype, c3.act)
-    pin = lambda shape: torch.zeros(shape, dtype=torch.bfloat16).pin_memory()
-    h1 = [pin((f, d)) for _ in range(5)] + [None] * (E - 5)
-    h3 = [pin((f, d)) for _ in range(5)] + [None] * (E - 5)
-    h2 = [pin((d, f)) for _ in range(5)] + [None] * (E - 5)
+    def pin(src):   # pinned host copy of a device matrix (real weight values: zeros would flatter the clock)
+        t = torch.empty(src.shape, dtype=src.dtype).pin_memory()
+        t.copy_(src)
+        return t
+    h1 = [pin(dev3.w1_slots[i % 4]) for i in range(5)] + [None] * (E - 5)
+    h3 = [pin(dev3.w3_slots[i % 4]) for i in range(5)] + [None] * (E - 5)
+    h2 = [pin(dev3.w2_slots[i % 4]) for i in range(5)] + [None] * (E - 5)
     w1 = torch.empty((S, f, d), dtype=torch.bfloat16, device="cuda")
     w3, w2 = torch.empty_like(w1), torch.empty((S, d, f), dtype=torch.bfloat16, device="cuda")
     soe = torch.full((E,), -1, dtype=torch.int32, device="cuda")
@@ -152,6 +155,59 @@ def bench_load(torch, P, gen, c3, dev3, buf3):
                                            "layer_ms_per_step_meanwhile": fwd_ms},
            "note": "pinned host -> HBM through emoe_load_experts on a side stream; not part of tokens/s"}
     log(f"load: {res}")
+    del w1, w3, w2
+    torch.cuda.empty_cache()
+    res["stack_of_4_layers"] = bench_loader(torch, P, c3, dev3, buf3, h1, h3, h2)
+    return res
+
+
+def bench_loader(torch, P, c3, dev3, buf3, h1, h3, h2):
+    """Sections 3.3 / 4 on four Mixtral-shaped layers (4 slots each): the prompt that changes the residents
+    (two of four experts per layer, 2.8 GB in all) with the loads exposed (wait for all of them, then compute)
+    and hidden (compute starts at once; each layer waits for its own load only)."""
+    n_layers, S, E = 4, 4, c3.E
+    f, d = c3.d_ff, c3.d_model
+    desc = P.make_desc(c3.T, d, f, E, c3.k, S, c3.dtype, c3.act)
+    full = lambda h: [h[i % 5] for i in range(E)]     # every expert has host weights (five distinct buffers)
+    layers = []
+    for _ in range(n_layers):
+        w1 = torch.empty((S, f, d), dtype=torch.bfloat16, device="cuda")
+        layers.append(dict(desc=desc, host_w1=full(h1), host_w3=full(h3), host_w2=full(h2), w1_slots=w1,
+                           w3_slots=torch.empty_like(w1), w2_slots=torch.empty((S, d, f), dtype=torch.bfloat16, device="cuda"),
+                           slot_of_expert=torch.full((E,), -1, dtype=torch.int32, device="cuda"),
+                           expert_of_slot=torch.full((S,), -1, dtype=torch.int32, device="cuda")))
+    torch.cuda.synchronize()
+    loader = P.Loader(layers, 40)
+    index, action = loader.next_prompt()              # 4 of 8 experts fit: the first prompt needs a selection
+    assert action == P.EMOE_PROMPT_PREDICT
+    loader.update([[0, 1, 2, 3]] * n_layers)
+    loader.synchronize()
+
+    def prompt(exposed, selection):
+        t0 = time.perf_counter()
+        if selection is not None:
+            loader.update([selection] * n_layers)
+            if exposed:
+                loader.synchronize()
+        for i, l in enumerate(layers):
+            loader.layer_begin(i)
+            P.layer_forward(buf3, dev3.x, dev3.w_gate, dev3.gate_bias, l["slot_of_expert"], l["w1_slots"], l["w3_slots"],
+                            l["w2_slots"])
+            loader.layer_end(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    prompt(False, None)
+    plain = min(prompt(False, None) for _ in range(3))
+    exposed = prompt(True, [0, 1, 4, 5])
+    hidden = prompt(False, [0, 1, 2, 3])
+    exposed2 = prompt(True, [0, 1, 4, 5])
+    hidden2 = prompt(False, [0, 1, 2, 3])
+    loader.close()
+    res = {"layers": n_layers, "bytes_loaded_per_change": n_layers * 2 * 3 * f * d * 2,
+           "prompt_ms_no_load": plain, "prompt_ms_loads_exposed": min(exposed, exposed2),
+           "prompt_ms_loads_hidden": min(hidden, hidden2)}
+    log(f"loader: {res}")
     return res
 
 

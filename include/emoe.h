@@ -214,6 +214,62 @@ int emoe_select_experts(int32_t E, const double *expected, int32_t L, int32_t *s
 int emoe_plan_load(int32_t E, int32_t S, int32_t k, const int32_t *expert_of_slot_host, int32_t L,
                    const int32_t *selected, int32_t *expert_ids, int32_t *slot_ids, int32_t *n);
 
+/*
+ * Periodic loading for a stack of MoE layers (Section 3.3: requests are numbered
+ * 0, 1, 2, ...; for the first one all experts are loaded, for every p-th one the
+ * predictor is invoked and only the predicted experts are loaded, all others
+ * reuse the residents.  Section 4: a layer's load and the layer's computation
+ * are ordered against each other, and layer i+1's load begins only after layer
+ * i's has finished, so that loads never compete for the host link).
+ *
+ * emoe_prompt_action: the rule alone (host only, no GPU needed).  Returns
+ * EMOE_PROMPT_LOAD_ALL for index 0 if all experts fit the slots (S == E in every
+ * layer; otherwise index 0 needs a prediction like a p-th prompt),
+ * EMOE_PROMPT_PREDICT if index % period == 0, else EMOE_PROMPT_REUSE; negative
+ * emoe_status on a bad argument.
+ *
+ * emoe_loader: the object that applies it.  It owns one side stream (default
+ * priority), two events per layer and the host mirrors of the slot maps, which
+ * start empty; everything in emoe_loader_layer stays the caller's and must
+ * outlive the loader (host_w*: arrays [E] of pinned host pointers, as for
+ * emoe_load_experts; desc.T is ignored).  Not thread safe.
+ *   create        EMOE_ERR_DEVICE if stream or events cannot be created.
+ *   next_prompt   numbers the prompt and reports its action; for LOAD_ALL it has
+ *                 already enqueued the loads (expert e into slot e, layer after
+ *                 layer).  For PREDICT the caller obtains the prediction and
+ *                 calls update before the prompt's first layer.
+ *   update        selected[i] = L[i] expert ids of layer i in descending
+ *                 workload order.  Plans every layer (emoe_plan_load) and then
+ *                 enqueues the changed layers' loads on the side stream in
+ *                 layer order; each waits until that layer's last forward has
+ *                 released its slots.  On an error nothing has been enqueued.
+ *   layer_begin   call before layer i's forward: makes compute_stream wait for
+ *                 the layer's pending load, if any (no stale weights).
+ *   layer_end     call after layer i's forward: marks on compute_stream the
+ *                 point after which the layer's slots may be overwritten.
+ *   residents     copies layer i's host mirror expert_of_slot [S].
+ *   synchronize   blocks the host until every enqueued load has finished.
+ *   destroy       synchronizes the side stream, then frees the object.
+ */
+enum { EMOE_PROMPT_REUSE = 0, EMOE_PROMPT_LOAD_ALL = 1, EMOE_PROMPT_PREDICT = 2 };
+typedef struct emoe_loader emoe_loader;
+typedef struct {
+    emoe_layer_desc desc;
+    const void *const *host_w1, *const *host_w3, *const *host_w2;
+    void *w1_slots, *w3_slots, *w2_slots;
+    int32_t *slot_of_expert, *expert_of_slot;
+} emoe_loader_layer;
+
+int emoe_prompt_action(int64_t prompt_index, int32_t period, int32_t all_experts_fit);
+int emoe_loader_create(int32_t n_layers, const emoe_loader_layer *layers, int32_t period, emoe_loader **out);
+int emoe_loader_destroy(emoe_loader *loader);
+int emoe_loader_next_prompt(emoe_loader *loader, int64_t *prompt_index, int32_t *action);
+int emoe_loader_update(emoe_loader *loader, const int32_t *const *selected, const int32_t *L);
+int emoe_loader_layer_begin(emoe_loader *loader, int32_t layer, void *compute_stream);
+int emoe_loader_layer_end(emoe_loader *loader, int32_t layer, void *compute_stream);
+int emoe_loader_residents(const emoe_loader *loader, int32_t layer, int32_t *expert_of_slot_host);
+int emoe_loader_synchronize(emoe_loader *loader);
+
 #ifdef __cplusplus
 }
 #endif

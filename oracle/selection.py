@@ -89,3 +89,16 @@ def plan_load(expert_of_slot: Sequence[int], selected: Sequence[int]) -> Tuple[L
             experts.append(-1)
             slots.append(s)
     return experts, slots, np.asarray(eos, dtype=np.int32)
+
+
+REUSE, LOAD_ALL, PREDICT = 0, 1, 2
+
+
+def prompt_action(index: int, period: int, all_experts_fit: bool = True) -> int:
+    """Section 3.3: requests are numbered 0, 1, 2, ...; the first loads every expert; every p-th one
+    invokes the predictor and loads what it predicts; the others reuse what is loaded.
+    Reading where the paper is silent: if the slots cannot hold all experts, the first request
+    needs a prediction too."""
+    if index == 0:
+        return LOAD_ALL if all_experts_fit else PREDICT
+    return PREDICT if index % period == 0 else REUSE

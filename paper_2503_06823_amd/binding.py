@@ -24,7 +24,9 @@ ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
 
 EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_route_observe", "emoe_permute",
            "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_combine", "emoe_load_experts", "emoe_expected_tokens",
-           "emoe_select_experts", "emoe_plan_load")
+           "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
+           "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
+           "emoe_loader_residents", "emoe_loader_synchronize")
 
 
 class EmoeLayerDesc(ctypes.Structure):
@@ -229,3 +231,80 @@ def emoe_plan_load(E, S, k, expert_of_slot_host, selected, check=True):
     rc = lib().emoe_plan_load(int(E), int(S), int(k), eos, L, sel, ids, slots, ctypes.byref(n))
     _check(rc, "emoe_plan_load", check)
     return (list(ids)[:n.value], list(slots)[:n.value]) if rc == EMOE_OK else rc
+
+
+EMOE_PROMPT_REUSE, EMOE_PROMPT_LOAD_ALL, EMOE_PROMPT_PREDICT = 0, 1, 2
+
+
+def emoe_prompt_action(prompt_index: int, period: int, all_experts_fit: bool) -> int:
+    return lib().emoe_prompt_action(ctypes.c_int64(int(prompt_index)), int(period), 1 if all_experts_fit else 0)
+
+
+class EmoeLoaderLayer(ctypes.Structure):
+    _fields_ = [("desc", EmoeLayerDesc),
+                ("host_w1", ctypes.c_void_p), ("host_w3", ctypes.c_void_p), ("host_w2", ctypes.c_void_p),
+                ("w1_slots", ctypes.c_void_p), ("w3_slots", ctypes.c_void_p), ("w2_slots", ctypes.c_void_p),
+                ("slot_of_expert", ctypes.c_void_p), ("expert_of_slot", ctypes.c_void_p)]
+
+
+class Loader:
+    """Handle of an emoe_loader.  `layers`: one dict per MoE layer with keys desc, host_w1, host_w3, host_w2
+    (sequences of E pinned host tensors), w1_slots, w3_slots, w2_slots, slot_of_expert, expert_of_slot (device
+    tensors).  Keeps references to everything it handed to the library."""
+
+    def __init__(self, layers, period: int):
+        self._keep = []
+        arr = (EmoeLoaderLayer * max(len(layers), 1))()
+        for i, l in enumerate(layers):
+            d = l["desc"]
+            ptrs = [_ptr_array(l[k], d.E) for k in ("host_w1", "host_w3", "host_w2")]
+            self._keep.append((l, ptrs))
+            cast = lambda a: ctypes.cast(a, ctypes.c_void_p) if a is not None else None
+            arr[i] = EmoeLoaderLayer(d, cast(ptrs[0]), cast(ptrs[1]), cast(ptrs[2]), _ptr(l["w1_slots"]),
+                                     _ptr(l.get("w3_slots")), _ptr(l["w2_slots"]), _ptr(l["slot_of_expert"]),
+                                     _ptr(l["expert_of_slot"]))
+        self.n_layers = len(layers)
+        self._slots = [l["desc"].S for l in layers]
+        self._h = ctypes.c_void_p(0)
+        rc = lib().emoe_loader_create(len(layers), arr, int(period), ctypes.byref(self._h))
+        if rc != EMOE_OK:
+            self._h = None
+            raise EmoeError(rc, "emoe_loader_create")
+
+    def next_prompt(self):
+        """-> (prompt index, action)"""
+        idx, act = ctypes.c_int64(0), ctypes.c_int32(0)
+        _check(lib().emoe_loader_next_prompt(self._h, ctypes.byref(idx), ctypes.byref(act)), "emoe_loader_next_prompt", True)
+        return idx.value, act.value
+
+    def update(self, selected, check=True) -> int:
+        """`selected`: per layer, the expert ids in descending workload order."""
+        rows = [_i32_array(list(r)) for r in selected]
+        ptrs = (ctypes.c_void_p * max(len(rows), 1))(*[ctypes.cast(r, ctypes.c_void_p) for r in rows])
+        L = _i32_array([len(r) for r in selected])
+        return _check(lib().emoe_loader_update(self._h, ptrs, L), "emoe_loader_update", check)
+
+    def layer_begin(self, layer: int, stream=None) -> int:
+        return _check(lib().emoe_loader_layer_begin(self._h, int(layer), _stream(stream)), "emoe_loader_layer_begin", True)
+
+    def layer_end(self, layer: int, stream=None) -> int:
+        return _check(lib().emoe_loader_layer_end(self._h, int(layer), _stream(stream)), "emoe_loader_layer_end", True)
+
+    def residents(self, layer: int):
+        out = (ctypes.c_int32 * self._slots[layer])()
+        _check(lib().emoe_loader_residents(self._h, int(layer), out), "emoe_loader_residents", True)
+        return list(out)
+
+    def synchronize(self) -> int:
+        return _check(lib().emoe_loader_synchronize(self._h), "emoe_loader_synchronize", True)
+
+    def close(self):
+        if self._h:
+            lib().emoe_loader_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

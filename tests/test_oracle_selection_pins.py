@@ -130,3 +130,15 @@ def test_with_every_expert_resident_the_workload_is_the_permutation_s_row_count(
     res = oracle.layer_forward(inp, with_ffn=False)
     w = sel.observed_workload(oracle.route_unrestricted(res.logits, c.k), c.E)
     assert np.array_equal(w, res.permutation.slot_counts[inp.slot_of_expert])
+
+
+def test_period_rule_of_section_3_3():
+    """First request: all experts; then the predictor once per p requests (p = 40 in the paper's overhead study)."""
+    acts = [sel.prompt_action(i, 40) for i in range(121)]
+    assert acts[0] == sel.LOAD_ALL
+    assert [i for i, a in enumerate(acts) if a == sel.PREDICT] == [40, 80, 120]
+    assert all(a == sel.REUSE for i, a in enumerate(acts) if i % 40)
+    for p in (1, 2, 7):
+        n = 50
+        assert sum(sel.prompt_action(i, p) == sel.PREDICT for i in range(n)) == (n - 1) // p
+    assert sel.prompt_action(0, 5, all_experts_fit=False) == sel.PREDICT

@@ -74,3 +74,33 @@ def test_selection_argument_errors():
     assert P.emoe_plan_load(8, 4, 2, [0, 1, 2, 3], [4, 4], check=False) == P.EMOE_ERR_RESIDENT           # repeated
     assert P.emoe_plan_load(8, 4, 2, [0, 0, 2, 3], [4, 5], check=False) == P.EMOE_ERR_RESIDENT           # bad map
     assert P.lib().emoe_select_experts(2, None, 1, None) == P.EMOE_ERR_NULL
+
+
+def test_period_rule_matches_the_oracle():
+    for period in (1, 2, 3, 40, 57):
+        for fit in (True, False):
+            for i in range(0, 200):
+                assert P.emoe_prompt_action(i, period, fit) == sel.prompt_action(i, period, fit)
+    assert P.emoe_prompt_action(-1, 3, True) == P.EMOE_ERR_SHAPE
+    assert P.emoe_prompt_action(5, 0, True) == P.EMOE_ERR_SHAPE
+
+
+def test_loader_rejects_bad_arguments_before_touching_the_device():
+    lib = P.lib()
+    import ctypes
+    h = ctypes.c_void_p(0)
+    assert lib.emoe_loader_create(1, None, 3, ctypes.byref(h)) == P.EMOE_ERR_NULL
+    d = P.make_desc(0, 64, 64, 4, 2, 4, "bf16", "swiglu")
+    w = [np.zeros(8, np.uint16) for _ in range(4)]
+    good = dict(desc=d, host_w1=w, host_w3=w, host_w2=w, w1_slots=4096, w3_slots=4096, w2_slots=4096,
+                slot_of_expert=4096, expert_of_slot=4096)
+    for bad, code in ((dict(good, w3_slots=None), P.EMOE_ERR_NULL), (dict(good, slot_of_expert=None), P.EMOE_ERR_NULL),
+                      (dict(good, desc=P.make_desc(0, 60, 64, 4, 2, 4, "bf16", "swiglu")), P.EMOE_ERR_UNSUPPORTED)):
+        with pytest.raises(P.EmoeError) as ei:
+            P.Loader([bad], 3)
+        assert ei.value.status == code
+    with pytest.raises(P.EmoeError) as ei:
+        P.Loader([good], 0)
+    assert ei.value.status == P.EMOE_ERR_SHAPE
+    assert lib.emoe_loader_destroy(None) == P.EMOE_ERR_NULL
+    assert lib.emoe_loader_layer_begin(None, 0, None) == P.EMOE_ERR_NULL

@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the resident-expert MoE layer on one MI355X.
 
-A step is one pass of the whole hot path (route -> permute -> expert FFN -> combine) over one
+A step is one pass of the whole hot path (route -> permute -> expert FFN, which gathers the token
+rows itself -> combine) over one
 batch of synthetic input that is already resident in HBM.  The headline workload is the
 Mixtral-8x7B-shaped prefill layer (4096 tokens, 4 of 8 experts resident); the decode step
 (64 tokens, 6 of 8 resident) is measured in the same run and reported under "decode".
@@ -42,11 +43,12 @@ def timed_steps(torch, P, dev, buf, steps, warmup, weight_sets):
         if events: events[0].record()
         P.emoe_route(d, dev.x, dev.w_gate, dev.gate_bias, dev.slot_of_expert, buf.topk_expert, buf.topk_weight)
         P.emoe_permute(d, dev.x, buf.topk_expert, dev.slot_of_expert, buf.slot_counts, buf.slot_offsets, buf.perm,
-                       buf.inv_perm, buf.x_perm, buf.permute_ws, buf.permute_ws.numel())
+                       buf.inv_perm, None, buf.permute_ws, buf.permute_ws.numel())     # indices only
         if events: events[1].record()
-        P.emoe_expert_ffn_pass(d, 1, buf.x_perm, buf.slot_offsets, w1, w3, w2, buf.y_perm, buf.ffn_ws, ws_n)
+        # the FFN reads the token rows through perm (no x_perm copy)
+        P.emoe_expert_ffn_gather_pass(d, 1, dev.x, buf.perm, buf.slot_offsets, w1, w3, w2, buf.y_perm, buf.ffn_ws, ws_n)
         if events: events[2].record()
-        P.emoe_expert_ffn_pass(d, 2, buf.x_perm, buf.slot_offsets, w1, w3, w2, buf.y_perm, buf.ffn_ws, ws_n)
+        P.emoe_expert_ffn_gather_pass(d, 2, dev.x, buf.perm, buf.slot_offsets, w1, w3, w2, buf.y_perm, buf.ffn_ws, ws_n)
         if events: events[3].record()
         P.emoe_combine(d, buf.y_perm, buf.inv_perm, buf.topk_weight, buf.out)
         if events: events[4].record()

@@ -108,6 +108,8 @@ int emoe_route_observe(const emoe_layer_desc *desc, const void *x, const void *w
  *   inv_perm[a] = r,
  *   x_perm[r,:]     = x[perm[r] / k, :]   (bit copy).
  * All outputs dev; ws dev, ws_bytes >= permute_ws_bytes of emoe_workspace_bytes.
+ * x_perm may be NULL (then x may be NULL too): only the indices are produced, for
+ * a caller that goes on with emoe_expert_ffn_gather and never needs the copy.
  */
 int emoe_permute(const emoe_layer_desc *desc, const void *x, const int32_t *topk_expert,
                  const int32_t *slot_of_expert, int32_t *slot_counts, int32_t *slot_offsets, int32_t *perm,
@@ -137,6 +139,22 @@ int emoe_expert_ffn(const emoe_layer_desc *desc, const void *x_perm, const int32
 int emoe_expert_ffn_pass(const emoe_layer_desc *desc, int32_t pass, const void *x_perm,
                          const int32_t *slot_offsets, const void *w1_slots, const void *w3_slots,
                          const void *w2_slots, void *y_perm, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * emoe_expert_ffn with the row gather folded into the first product's operand
+ * load: grouped row r is read as x[perm[r] / k, :] straight from the token matrix,
+ * so x_perm is neither written nor read (it is the dominant glue traffic of a
+ * layer with many small experts).  Same result as emoe_permute's x_perm followed
+ * by emoe_expert_ffn, bit for bit.  x [T,d] dev, perm [A] dev (from emoe_permute);
+ * everything else as emoe_expert_ffn.  emoe_expert_ffn_gather_pass: its two
+ * halves, as emoe_expert_ffn_pass.
+ */
+int emoe_expert_ffn_gather(const emoe_layer_desc *desc, const void *x, const int32_t *perm,
+                           const int32_t *slot_offsets, const void *w1_slots, const void *w3_slots,
+                           const void *w2_slots, void *y_perm, void *ws, size_t ws_bytes, void *stream);
+int emoe_expert_ffn_gather_pass(const emoe_layer_desc *desc, int32_t pass, const void *x, const int32_t *perm,
+                                const int32_t *slot_offsets, const void *w1_slots, const void *w3_slots,
+                                const void *w2_slots, void *y_perm, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Gate-weighted combine back to token order (Section 1):

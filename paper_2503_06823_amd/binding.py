@@ -23,7 +23,7 @@ DTYPES = {"f32": EMOE_F32, "bf16": EMOE_BF16}
 ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
 
 EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_route_observe", "emoe_permute",
-           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_combine", "emoe_load_experts", "emoe_expected_tokens",
+           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_combine", "emoe_load_experts", "emoe_expected_tokens",
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
            "emoe_loader_residents", "emoe_loader_synchronize")
@@ -155,6 +155,22 @@ def emoe_expert_ffn_pass(desc, which, x_perm, slot_offsets, w1_slots, w3_slots, 
                                     _ptr(w3_slots), _ptr(w2_slots), _ptr(y_perm), _ptr(ws), int(ws_bytes),
                                     _stream(stream))
     return _check(rc, "emoe_expert_ffn_pass", check)
+
+
+def emoe_expert_ffn_gather(desc, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes, stream=None,
+                           check=True) -> int:
+    rc = lib().emoe_expert_ffn_gather(ctypes.byref(desc), _ptr(x), _ptr(perm), _ptr(slot_offsets), _ptr(w1_slots),
+                                      _ptr(w3_slots), _ptr(w2_slots), _ptr(y_perm), _ptr(ws),
+                                      ctypes.c_size_t(int(ws_bytes)), _stream(stream))
+    return _check(rc, "emoe_expert_ffn_gather", check)
+
+
+def emoe_expert_ffn_gather_pass(desc, which, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+                                stream=None, check=True) -> int:
+    rc = lib().emoe_expert_ffn_gather_pass(ctypes.byref(desc), int(which), _ptr(x), _ptr(perm), _ptr(slot_offsets),
+                                           _ptr(w1_slots), _ptr(w3_slots), _ptr(w2_slots), _ptr(y_perm), _ptr(ws),
+                                           ctypes.c_size_t(int(ws_bytes)), _stream(stream))
+    return _check(rc, "emoe_expert_ffn_gather_pass", check)
 
 
 def emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream=None, check=True) -> int:

@@ -112,8 +112,8 @@ int emoe_permute(const emoe_layer_desc* desc, const void* x, const int32_t* topk
                  int32_t* inv_perm, void* x_perm, void* ws, size_t ws_bytes, void* stream) {
     int rc = validate_desc(desc);
     if (rc != EMOE_OK) return rc;
-    if (!x || !topk_expert || !slot_of_expert || !slot_counts || !slot_offsets || !perm || !inv_perm || !x_perm)
-        return EMOE_ERR_NULL;
+    if (!topk_expert || !slot_of_expert || !slot_counts || !slot_offsets || !perm || !inv_perm) return EMOE_ERR_NULL;
+    if (x_perm && !x) return EMOE_ERR_NULL;  // x_perm == NULL: indices only, no row copy
     if (!ws || ws_bytes < permute_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (desc->T == 0) {  // no assignments: every slot is empty
@@ -126,7 +126,7 @@ int emoe_permute(const emoe_layer_desc* desc, const void* x, const int32_t* topk
     return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
 }
 
-static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void* x_perm,
+static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void* x_perm, const int32_t* perm,
                              const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
                              const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
     int rc = validate_desc(desc);
@@ -137,20 +137,21 @@ static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void
     if (!ws || ws_bytes < ffn_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
     if (desc->T == 0) return EMOE_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const RowGather gather{perm, desc->k, desc->T};  // perm == nullptr: x_perm holds the grouped rows themselves
     hipError_t e;
     if (desc->dtype == EMOE_F32)
-        e = launch_ffn_f32(*desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+        e = launch_ffn_f32(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
     else if (ffn_use_stream_path(*desc))
-        e = launch_ffn_bf16_stream(*desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+        e = launch_ffn_bf16_stream(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
     else
-        e = launch_ffn_bf16_tiled(*desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+        e = launch_ffn_bf16_tiled(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
     return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
 }
 
 int emoe_expert_ffn(const emoe_layer_desc* desc, const void* x_perm, const int32_t* slot_offsets,
                     const void* w1_slots, const void* w3_slots, const void* w2_slots, void* y_perm, void* ws,
                     size_t ws_bytes, void* stream) {
-    return expert_ffn_passes(desc, 3, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+    return expert_ffn_passes(desc, 3, x_perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
                              stream);
 }
 
@@ -158,7 +159,24 @@ int emoe_expert_ffn_pass(const emoe_layer_desc* desc, int32_t pass, const void* 
                          const void* w1_slots, const void* w3_slots, const void* w2_slots, void* y_perm, void* ws,
                          size_t ws_bytes, void* stream) {
     if (pass != 1 && pass != 2) return EMOE_ERR_SHAPE;
-    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws,
+    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x_perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots,
+                             y_perm, ws, ws_bytes, stream);
+}
+
+int emoe_expert_ffn_gather(const emoe_layer_desc* desc, const void* x, const int32_t* perm,
+                           const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
+                           const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
+    if (!perm) return EMOE_ERR_NULL;
+    return expert_ffn_passes(desc, 3, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+                             stream);
+}
+
+int emoe_expert_ffn_gather_pass(const emoe_layer_desc* desc, int32_t pass, const void* x, const int32_t* perm,
+                                const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
+                                const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
+    if (pass != 1 && pass != 2) return EMOE_ERR_SHAPE;
+    if (!perm) return EMOE_ERR_NULL;
+    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws,
                              ws_bytes, stream);
 }
 

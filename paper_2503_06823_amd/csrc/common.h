@@ -64,12 +64,20 @@ hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t
                           int32_t* inv_perm, void* x_perm, void* ws, hipStream_t st);
 hipError_t launch_combine(const emoe_layer_desc& d, const void* y_perm, const int32_t* inv_perm,
                           const float* topk_weight, void* out, hipStream_t st);
-hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets, const void* w1,
+// Where pass 1 finds the token row of grouped row r: in x_perm[r] (perm == nullptr), or in
+// x[perm[r] / k] (the gather folded into the operand load; `rows` = T bounds the buffer).
+struct RowGather {
+    const int32_t* perm;
+    int k;
+    int rows;
+};
+
+hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets, const void* w1,
                           const void* w3, const void* w2, void* y_perm, void* ws, int passes, hipStream_t st);
-hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
+hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets,
                                  const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                  int passes, hipStream_t st);
-hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
+hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets,
                                   const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                   int passes, hipStream_t st);
 hipError_t launch_fill_i32(int32_t* p, int n, int32_t value, hipStream_t st);

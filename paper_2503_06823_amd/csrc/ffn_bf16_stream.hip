@@ -60,7 +60,7 @@ __device__ __forceinline__ void barrier_keep_loads() {
 
 // grid.x = S * ceil(N / BNO) workgroups, BNO = output columns per workgroup (32 SwiGLU, else 64).
 template <int EPI, int WR, bool KTAIL>
-__global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const bf16_t* __restrict__ a,
+__global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
                                                            const int32_t* __restrict__ offsets,
                                                            const bf16_t* __restrict__ b0,
                                                            const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const 
     // ---- global -> LDS: instruction (w, i) fills RPI tile rows; lane l lands in row l/CPR, chunk
     //      position l%CPR and fetches global chunk (l%CPR) ^ (row&15) ------------------------------
     const int l_rin = lane / CPR, l_pos = lane % CPR;
-    const uint32_t a_bytes = (uint32_t)rows_total * (uint32_t)K * 2u;
+    const uint32_t a_bytes = (uint32_t)(gather.perm != nullptr ? gather.rows : rows_total) * (uint32_t)K * 2u;
     const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
     uint32_t w_voff[LW];
     int w_chunk[LW];
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const 
             x_chunk[i] = l_pos ^ (tr & 15);
             int r = tok0 + tr;
             r = r < row_end ? r : row_end - 1;
+            if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
             x_voff[i] = ((uint32_t)r * (uint32_t)K + x_chunk[i] * 8) * 2u;
         }
         auto issue_tile = [&](int stage, int k0) {
@@ -224,31 +225,32 @@ __global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const 
 }
 
 template <int EPI, int WR>
-hipError_t launch_wr(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
+hipError_t launch_wr(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
                      int N, int K, hipStream_t st) {
     constexpr int BNO = EPI == kSwiglu ? WR / 2 : WR;
     const int n_units = (N + BNO - 1) / BNO;
     const unsigned blocks = (unsigned)(S * n_units);
     if (K % BK == 0)
-        stream_gemm_bf16<EPI, WR, false><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
+        stream_gemm_bf16<EPI, WR, false><<<blocks, 256, 0, st>>>(a, gather, offsets, b0, b1, c, S, N, K, n_units);
     else
-        stream_gemm_bf16<EPI, WR, true><<<blocks, 256, 0, st>>>(a, offsets, b0, b1, c, S, N, K, n_units);
+        stream_gemm_bf16<EPI, WR, true><<<blocks, 256, 0, st>>>(a, gather, offsets, b0, b1, c, S, N, K, n_units);
     return hipGetLastError();
 }
 
 template <int EPI>
-hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
+hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c, int S,
                       int N, int K, hipStream_t st) {
     if constexpr (EPI != kSwiglu) {
         // fewer 64-row units than workgroup slots (2 per CU): halve the unit so the whole chip streams
-        if ((long long)S * ((N + 63) / 64) < 2 * 256) return launch_wr<EPI, 32>(a, offsets, b0, b1, c, S, N, K, st);
+        if ((long long)S * ((N + 63) / 64) < 2 * 256) return launch_wr<EPI, 32>(a, gather, offsets, b0, b1, c, S, N, K, st);
     }
-    return launch_wr<EPI, 64>(a, offsets, b0, b1, c, S, N, K, st);
+    return launch_wr<EPI, 64>(a, gather, offsets, b0, b1, c, S, N, K, st);
 }
 
 }  // namespace
 
-hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
+hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, RowGather gather,
+                                  const int32_t* offsets,
                                   const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                   int passes, hipStream_t st) {
     bf16_t* h = reinterpret_cast<bf16_t*>(static_cast<uint8_t*>(ws) + ffn_ws_layout(d).h);
@@ -256,12 +258,12 @@ hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, 
     hipError_t e = hipSuccess;
     if (!(passes & 1)) {
     } else if (d.act == EMOE_ACT_SWIGLU)
-        e = launch_one<kSwiglu>(xp, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h, d.S,
+        e = launch_one<kSwiglu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h, d.S,
                                 d.d_ff, d.d_model, st);
     else
-        e = launch_one<kRelu>(xp, offsets, static_cast<const bf16_t*>(w1), nullptr, h, d.S, d.d_ff, d.d_model, st);
+        e = launch_one<kRelu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), nullptr, h, d.S, d.d_ff, d.d_model, st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain>(h, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm), d.S,
+    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm), d.S,
                               d.d_model, d.d_ff, st);
 }
 

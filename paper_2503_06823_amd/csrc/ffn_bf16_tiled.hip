@@ -177,7 +177,7 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __rest
 }
 
 template <int EPI, bool KTAIL>
-__global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __restrict__ a,
+__global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
                                                          const int32_t* __restrict__ offsets,
                                                          const bf16_t* __restrict__ b0,
                                                          const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
     // lane-constant parts of the addressing
     const int l_row = lane >> 2;
     const int l_chunk = (lane & 3) ^ ((l_row >> 2) & 3);
-    const uint32_t a_bytes = (uint32_t)rows_total * (uint32_t)K * 2u;
+    const uint32_t a_bytes = (uint32_t)(gather.perm != nullptr ? gather.rows : rows_total) * (uint32_t)K * 2u;
     const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
     const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a, a_bytes);
     const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // upper wavefronts load the W3 half
@@ -249,6 +249,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             const int tr = (LPW * wave + i) * 16 + l_row;  // row of the tile
             int r = row0 + tr;
             r = r < row_end ? r : row_end - 1;
+            if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
             a_voff[i] = ((uint32_t)r * (uint32_t)K + l_chunk * 8) * 2u;
             int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
             n = n < N ? n : N - 1;
@@ -403,7 +404,7 @@ __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restric
 }
 
 template <int EPI, bool KTAIL>
-hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
+hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
                       float* partials, int S, int N, int K, int n_tiles, hipStream_t st) {
     auto kern = grouped_gemm_bf16<EPI, KTAIL>;
     static bool attr_set = false;
@@ -413,24 +414,25 @@ hipError_t launch_cfg(const bf16_t* a, const int32_t* offsets, const bf16_t* b0,
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles);
+    kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
     splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, reinterpret_cast<const int*>(partials),
                                                         partials + kPlanFloats, S, N, K, n_tiles, kPersistentGroups);
     return hipGetLastError();
 }
 
 template <int EPI>
-hipError_t launch_one(const bf16_t* a, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
+hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
                       float* partials, int S, int N, int K, hipStream_t st) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     const int n_tiles = (N + BNO - 1) / BNO;
-    if (K % BK == 0) return launch_cfg<EPI, false>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles, st);
-    return launch_cfg<EPI, true>(a, offsets, b0, b1, c, partials, S, N, K, n_tiles, st);
+    if (K % BK == 0) return launch_cfg<EPI, false>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles, st);
+    return launch_cfg<EPI, true>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles, st);
 }
 
 }  // namespace
 
-hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets,
+hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, RowGather gather,
+                                 const int32_t* offsets,
                                  const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                  int passes, hipStream_t st) {
     const FfnWs lay = ffn_ws_layout(d);
@@ -440,13 +442,13 @@ hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, c
     hipError_t e = hipSuccess;
     if (!(passes & 1)) {
     } else if (d.act == EMOE_ACT_SWIGLU)
-        e = launch_one<kSwiglu>(xp, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h,
+        e = launch_one<kSwiglu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h,
                                 partials, d.S, d.d_ff, d.d_model, st);
     else
-        e = launch_one<kRelu>(xp, offsets, static_cast<const bf16_t*>(w1), nullptr, h, partials, d.S, d.d_ff, d.d_model,
+        e = launch_one<kRelu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), nullptr, h, partials, d.S, d.d_ff, d.d_model,
                               st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain>(h, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm),
+    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm),
                               partials, d.S, d.d_model, d.d_ff, st);
 }
 

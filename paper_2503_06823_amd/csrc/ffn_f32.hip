@@ -30,7 +30,8 @@ __device__ __forceinline__ bool find_group(const int32_t* __restrict__ offsets, 
 }
 
 template <int EPI>
-__global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict__ a, const int32_t* __restrict__ offsets,
+__global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict__ a, RowGather gather,
+                                                        const int32_t* __restrict__ offsets,
                                                         const float* __restrict__ b0, const float* __restrict__ b1,
                                                         float* __restrict__ c, int S, int N, int K) {
     __shared__ float As[BK][BM + 4];
@@ -46,11 +47,13 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict_
     const int lr = tid >> 2, lk = (tid & 3) * 4;  // loader: row within tile, k offset
     const int tx = tid & 15, ty = tid >> 4;       // compute: 4 columns tx*4.., 4 rows ty*4..
     float acc0[4][4] = {}, acc1[4][4] = {};
+    int a_row = row0 + lr;  // row of `a` this thread loads
+    if (gather.perm != nullptr && a_row < row_end) a_row = gather.perm[a_row] / gather.k;
 
     for (int k0 = 0; k0 < K; k0 += BK) {
         float4 va = make_float4(0, 0, 0, 0), vb0 = va, vb1 = va;
         const bool kok = k0 + lk < K;
-        if (kok && row0 + lr < row_end) va = *reinterpret_cast<const float4*>(a + (size_t)(row0 + lr) * K + k0 + lk);
+        if (kok && row0 + lr < row_end) va = *reinterpret_cast<const float4*>(a + (size_t)a_row * K + k0 + lk);
         if (kok && n0 + lr < N) {
             vb0 = *reinterpret_cast<const float4*>(w0 + (size_t)(n0 + lr) * K + k0 + lk);
             if (EPI == kSwiglu) vb1 = *reinterpret_cast<const float4*>(w1 + (size_t)(n0 + lr) * K + k0 + lk);
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict_
 
 }  // namespace
 
-hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, const int32_t* offsets, const void* w1,
+hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets, const void* w1,
                           const void* w3, const void* w2, void* y_perm, void* ws, int passes, hipStream_t st) {
     const int A = d.T * d.k;
     float* h = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + ffn_ws_layout(d).h);
@@ -107,13 +110,13 @@ hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, const in
     const float* xp = static_cast<const float*>(x_perm);
     if (!(passes & 1)) {
     } else if (d.act == EMOE_ACT_SWIGLU)
-        grouped_gemm_f32<kSwiglu><<<g1, 256, 0, st>>>(xp, offsets, static_cast<const float*>(w1),
+        grouped_gemm_f32<kSwiglu><<<g1, 256, 0, st>>>(xp, gather, offsets, static_cast<const float*>(w1),
                                                       static_cast<const float*>(w3), h, d.S, d.d_ff, d.d_model);
     else
-        grouped_gemm_f32<kRelu><<<g1, 256, 0, st>>>(xp, offsets, static_cast<const float*>(w1), nullptr, h, d.S,
+        grouped_gemm_f32<kRelu><<<g1, 256, 0, st>>>(xp, gather, offsets, static_cast<const float*>(w1), nullptr, h, d.S,
                                                     d.d_ff, d.d_model);
     if (passes & 2)
-        grouped_gemm_f32<kPlain><<<g2, 256, 0, st>>>(h, offsets, static_cast<const float*>(w2), nullptr,
+        grouped_gemm_f32<kPlain><<<g2, 256, 0, st>>>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const float*>(w2), nullptr,
                                                      static_cast<float*>(y_perm), d.S, d.d_model, d.d_ff);
     return hipGetLastError();
 }

@@ -7,7 +7,8 @@
 //   2. scan     : per slot, exclusive prefix over the workgroups; then prefix over the slots
 //   3. place    : each workgroup ranks its assignments in order with wave ballots and writes
 //                 perm / inv_perm
-//   4. gather   : one wavefront per output row copies the token row, 16 bytes per lane
+//   4. gather   : one wavefront per output row copies the token row, 16 bytes per lane (left out
+//                 when the caller wants indices only)
 // An assignment whose expert is not resident (only possible when the caller broke emoe_route's
 // precondition) is left out: inv_perm = -1, and it appears in no slot.
 #include "common.h"
@@ -232,6 +233,7 @@ hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t
         place_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, offsets, perm,
                                                     inv_perm, A, d.E, d.S);
     }
+    if (x_perm == nullptr) return hipGetLastError();  // indices only: the FFN reads x through perm
     const int rows_per_block = kThreads / 64;
     const int g = (A + rows_per_block - 1) / rows_per_block;
     if (d.dtype == EMOE_F32)

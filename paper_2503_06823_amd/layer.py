@@ -75,13 +75,19 @@ class DeviceInputs:
 
 
 def layer_forward(buf: LayerBuffers, x, w_gate, gate_bias, slot_of_expert, w1_slots, w3_slots, w2_slots,
-                  stream=None) -> torch.Tensor:
-    """Enqueue the four calls on one stream; returns buf.out (no host synchronisation)."""
+                  stream=None, gather_in_ffn: bool = True) -> torch.Tensor:
+    """Enqueue the four calls on one stream; returns buf.out (no host synchronisation).
+    `gather_in_ffn`: the FFN reads the token rows through perm (buf.x_perm stays unwritten); otherwise
+    emoe_permute copies them into buf.x_perm first."""
     d = buf.desc
     B.emoe_route(d, x, w_gate, gate_bias, slot_of_expert, buf.topk_expert, buf.topk_weight, stream)
     B.emoe_permute(d, x, buf.topk_expert, slot_of_expert, buf.slot_counts, buf.slot_offsets, buf.perm, buf.inv_perm,
-                   buf.x_perm, buf.permute_ws, buf.permute_ws.numel(), stream)
-    B.emoe_expert_ffn(d, buf.x_perm, buf.slot_offsets, w1_slots, w3_slots, w2_slots, buf.y_perm, buf.ffn_ws,
-                      buf.ffn_ws.numel(), stream)
+                   None if gather_in_ffn else buf.x_perm, buf.permute_ws, buf.permute_ws.numel(), stream)
+    if gather_in_ffn:
+        B.emoe_expert_ffn_gather(d, x, buf.perm, buf.slot_offsets, w1_slots, w3_slots, w2_slots, buf.y_perm,
+                                 buf.ffn_ws, buf.ffn_ws.numel(), stream)
+    else:
+        B.emoe_expert_ffn(d, buf.x_perm, buf.slot_offsets, w1_slots, w3_slots, w2_slots, buf.y_perm, buf.ffn_ws,
+                          buf.ffn_ws.numel(), stream)
     B.emoe_combine(d, buf.y_perm, buf.inv_perm, buf.topk_weight, buf.out, stream)
     return buf.out

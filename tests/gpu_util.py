@@ -54,9 +54,20 @@ class DeviceLayer:
         self.w2 = to_dev(inp.w2_slots, cfg.dtype, device)
         self.buf = P.LayerBuffers.allocate(self.desc, device)
 
-    def forward(self, stream=None):
+    def forward(self, stream=None, gather_in_ffn=False):
+        """gather_in_ffn=False also fills buf.x_perm (which the permutation checks compare)."""
         return P.layer_forward(self.buf, self.x, self.w_gate, self.gate_bias, self.slot_of_expert, self.w1, self.w3,
-                               self.w2, stream)
+                               self.w2, stream, gather_in_ffn=gather_in_ffn)
+
+    def check_gather_path_is_identical(self):
+        """The FFN that reads token rows through perm must reproduce y_perm and out bit for bit."""
+        b = self.buf
+        y0, o0, h0 = b.y_perm.clone(), b.out.clone(), b.ffn_ws.clone()
+        b.y_perm.fill_(0); b.out.fill_(0); b.x_perm.fill_(0)
+        self.forward(gather_in_ffn=True)
+        torch.cuda.synchronize()
+        assert torch.equal(b.y_perm, y0) and torch.equal(b.out, o0)
+        assert not b.x_perm.any(), "the gather path must not touch x_perm"
 
 
 def rel_l2(got: np.ndarray, ref: np.ndarray) -> float:

@@ -64,6 +64,7 @@ def test_bad_descriptors_are_rejected_by_every_entry_point(kw, code):
     assert P.emoe_route_observe(d, p, p, None, p, p, p, p, stream=0, check=False) == code
     assert P.emoe_permute(d, p, p, p, p, p, p, p, p, p, 1 << 30, stream=0, check=False) == code
     assert P.emoe_expert_ffn(d, p, p, p, p, p, p, p, 1 << 30, stream=0, check=False) == code
+    assert P.emoe_expert_ffn_gather(d, p, p, p, p, p, p, p, p, 1 << 30, stream=0, check=False) == code
     assert P.emoe_combine(d, p, p, p, p, stream=0, check=False) == code
 
 
@@ -82,6 +83,9 @@ def test_null_pointers_and_small_workspace():
     assert P.emoe_expert_ffn(d, p, p, p, None, p, p, p, fws, stream=0, check=False) == P.EMOE_ERR_NULL  # SwiGLU needs W3
     assert P.emoe_expert_ffn(good(act="relu"), p, p, p, p, p, p, p, fws, stream=0, check=False) == P.EMOE_ERR_UNSUPPORTED
     assert P.emoe_expert_ffn(d, p, p, p, p, p, p, p, fws - 1, stream=0, check=False) == P.EMOE_ERR_WORKSPACE
+    assert P.emoe_expert_ffn_gather(d, p, None, p, p, p, p, p, p, fws, stream=0, check=False) == P.EMOE_ERR_NULL
+    assert P.emoe_expert_ffn_gather(d, p, p, p, p, p, p, p, p, fws - 1, stream=0, check=False) == P.EMOE_ERR_WORKSPACE
+    assert P.emoe_expert_ffn_gather_pass(d, 3, p, p, p, p, p, p, p, p, fws, stream=0, check=False) == P.EMOE_ERR_SHAPE
     assert P.emoe_combine(d, p, None, p, p, stream=0, check=False) == P.EMOE_ERR_NULL
 
 

@@ -37,3 +37,4 @@ def test_full_size_workload(gpu_device, name):
     assert int(dl.buf.slot_offsets[-1]) == cfg.T * cfg.k
     tw = dl.buf.topk_weight
     assert torch.allclose(tw.sum(dim=1), torch.ones(cfg.T, device=tw.device), atol=1e-5)
+    dl.check_gather_path_is_identical()       # the configuration bench.py times reads x through perm

@@ -54,6 +54,7 @@ def test_layer_matches_oracle(gpu_device, c, shuffle):
     torch.cuda.synchronize()
     check_routing_and_permutation(dl, ref)
     check_outputs(dl, ref)
+    dl.check_gather_path_is_identical()
 
 
 def test_each_call_alone_on_oracle_inputs(gpu_device):

@@ -221,6 +221,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the upload measurement and the C5 / C2 workloads")
+    ap.add_argument("--more-shapes", action="store_true",
+                    help="also time a Mixtral-8x22B-shaped prefill layer and an OpenMoE-shaped layer")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = size the sample for about 15 s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy, so that a hardware-counter run of this "
@@ -314,6 +316,14 @@ def main():
         result["c2"] = other_config(torch, P, gen, gen.C2, 40, 8, 4,
                                     "C2 Switch-style layer: T=1024 d_model=768 d_ff=3072 E=64 top-1 ReLU, 16 of 64 resident, "
                                     "Zipf(1.1) gate bias, bf16; 4 rotating copies of the slot buffers")
+
+    if args.more_shapes:
+        result["x1"] = other_config(torch, P, gen, gen.X1, 10, 3, 1,
+                                    "X1 Mixtral-8x22B-shaped prefill layer: T=4096 d_model=6144 d_ff=16384 E=8 top-2 "
+                                    "SwiGLU, 4 of 8 resident, bf16")
+        result["x2"] = other_config(torch, P, gen, gen.X2, 20, 5, 1,
+                                    "X2 OpenMoE-shaped layer: T=2048 d_model=2048 d_ff=8192 E=32 top-2 SwiGLU, 16 of 32 "
+                                    "resident, Zipf(1.1) gate bias, bf16")
 
     # ---------------- the oracle on the host cores, on a bounded sample of the prefill workload ------------
     if not args.no_cpu_baseline:

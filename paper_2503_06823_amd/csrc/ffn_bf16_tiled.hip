@@ -13,19 +13,26 @@
 // activation is applied in registers.  The weight rows go on the MFMA's row operand: a lane then
 // owns four consecutive output columns of one token and stores them as one 8-byte write.
 //
-// Data movement: both operands are K-contiguous in memory.  K is walked in tiles of 32; a tile
-// (256 + 256 rows x 64 bytes = 32 KiB) goes from global memory straight into LDS with
-// buffer_load_dwordx4 ... lds (no staging registers, no LDS store instructions), four LDS stages
-// deep, so up to three tiles are in flight while one is multiplied.  Each load instruction fills
-// 1 KiB of LDS contiguously (16 rows x 64 bytes); the 16-byte chunk c of row r is stored at chunk
-// position c ^ ((r >> 2) & 3), chosen by which global chunk a lane fetches, which makes the MFMA
-// fragment reads (32 rows x one chunk per ds_read_b128) bank-conflict free without padding.
-// Buffer addressing gives a uniform (scalar) K offset plus a per-lane row offset, so the loop has
-// no address arithmetic; in the K tail, chunks past K are fetched out of range and arrive as zeros.
+// Data movement: both operands are K-contiguous in memory.  K is walked in tiles of 64, so that a
+// tile row is one whole 128-byte cache line (with 64-byte rows every line is requested twice, by
+// consecutive K tiles; halving the requests to L2 was worth 8-15 % here, where the kernel runs at
+// the chip's power limit).  An operand tile (256 rows x 128 bytes = 32 KiB) goes from global memory
+// straight into LDS with buffer_load_dwordx4 ... lds (no staging registers, no LDS store
+// instructions).  LDS is a ring of five operand tiles - token rows of K tile t in slot 2t mod 5,
+// weight rows in slot 2t+1 mod 5 - so one and a half K tiles are in flight while one is multiplied.
+// Each load instruction fills 1 KiB of LDS contiguously (8 rows x 128 bytes); the 16-byte chunk c
+// of row r is stored at chunk position c ^ ((r >> 1) & 7), chosen by which global chunk a lane
+// fetches, which makes the MFMA fragment reads (32 rows x one chunk per ds_read_b128) bank-conflict
+// free without padding.  Buffer addressing gives a uniform (scalar) K offset plus a per-lane row
+// offset, so the loop has no address arithmetic; in the K tail, chunks past K are fetched out of
+// range and arrive as zeros.
 //
-// Schedule per K tile (two MFMA steps of 16 each): fragment reads for the next step and the loads
-// of tile t+3 are slotted one by one between the MFMAs, so no memory instruction waits in a full
-// queue while the matrix pipe idles.  One barrier per tile, placed between the two steps.
+// Schedule per K tile (four MFMA steps of 16 each): fragment reads for the next step and the loads
+// of tile t+2 are slotted one by one between the MFMAs, so no memory instruction waits in a full
+// queue while the matrix pipe idles.  One barrier per tile, before its last step.
+//
+// Epilogue: results go through LDS so that they leave as whole 256- or 512-byte row segments (see
+// epilogue()); accumulators are read from their AGPRs one block at a time.
 //
 // Ragged groups: group sizes live on the device.  The launch is persistent (one workgroup per CU);
 // every workgroup derives the list of (slot, m-tile, n-tile) tiles from slot_offsets and takes its
@@ -46,12 +53,12 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int BM = 256;                     // tokens per tile
 constexpr int BR = 256;                     // weight rows per tile (SwiGLU: 128 of W1 + 128 of W3)
-constexpr int BK = 32;                      // K elements per tile
-constexpr int ROW_BYTES = BK * 2;           // 64
-constexpr int TILE_BYTES = BM * ROW_BYTES;  // 16 KiB per operand
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;
-constexpr int STAGES = 4;
-constexpr size_t LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KiB
+constexpr int BK = 64;                      // K elements per tile
+constexpr int ROW_BYTES = BK * 2;           // 128: a tile row is one whole cache line
+constexpr int TILE_BYTES = BM * ROW_BYTES;  // 32 KiB per operand
+constexpr int SLOTS = 5;                    // LDS ring of operand tiles: x(t), w(t), x(t+1), w(t+1), x(t+2), ...
+constexpr size_t LDS_BYTES = SLOTS * TILE_BYTES;  // 160 KiB, all of a CU's LDS
+constexpr int KSTEPS = BK / 16;             // MFMA K-steps per tile
 constexpr int XCDS = 8;
 constexpr int kPersistentGroups = 256;  // one workgroup per CU
 constexpr int kMaxSplits = 8;           // K pieces per leftover tile, at most
@@ -61,8 +68,8 @@ constexpr int NW = 4;            // wavefronts per workgroup, arranged 2 (tokens
 constexpr int WN = NW / 2;
 constexpr int TB = 4;            // 32-token blocks per wavefront (128 tokens)
 constexpr int WB = BR / WN / 32; // 32-row weight blocks per wavefront
-constexpr int LPW = 16 / NW;     // load instructions per wavefront, per tile and operand
-constexpr int LOADS = 2 * LPW;   // ... per tile
+constexpr int RPI = 1024 / ROW_BYTES;      // tile rows filled by one load instruction (8)
+constexpr int LPW = BM / RPI / NW;         // load instructions per wavefront, per tile and operand (8)
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
 
@@ -108,7 +115,7 @@ __device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ offsets, i
     p.rounds = p.tiles / G;
     p.left = p.tiles - p.rounds * G;
     int sp = p.left > 0 ? G / p.left : 1;
-    const int by_k = k_tiles / 16;  // at least 16 K tiles per piece
+    const int by_k = k_tiles / 8;  // at least 8 K tiles (512 elements) per piece
     sp = sp < by_k ? sp : by_k;
     sp = sp > kMaxSplits ? kMaxSplits : sp;
     p.splits = sp < 1 ? 1 : sp;
@@ -164,16 +171,66 @@ __device__ __forceinline__ void epilogue_block(const floatx16& gate, const float
     }
 }
 
+// Reads one accumulator where it lives (an AGPR).  Written out as an instruction so that the compiler
+// moves accumulators to VALU registers one at a time, where they are used, instead of copying all
+// 256 of them out at the end of the K loop (which needs every VGPR and spills the rest).
+__device__ __forceinline__ float acc_read(float a) {
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+// Epilogue of a whole tile.  The MFMA layout gives a lane 4 consecutive columns of 32 different
+// token rows, so storing straight from registers writes 16-byte scraps into 32 rows per
+// instruction.  Instead the wavefronts put their (activated, rounded) results into LDS as a
+// [256 token rows][BNO columns] bf16 image, and after a barrier every wavefront stores 64 of its
+// rows with 16 bytes per lane, 256 or 512 contiguous bytes per row.  In the image the 16-byte
+// chunk j of row r sits at chunk position j ^ (r & 15), which keeps both the 8-byte writes and the
+// 16-byte reads (nearly) free of bank conflicts.  All DMA loads have landed and all fragment reads
+// are done when this runs; the barrier at the end keeps the next tile's loads off the image.
 template <int EPI>
-__device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c, int row0, int row_end, int n0,
-                                         int N, int wm, int wn, int lane) {
+__device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c, char* lds, int row0,
+                                         int row_end, int n0, int N, int wm, int wn, int wave, int lane) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
+    constexpr int ROWB = BNO * 2;      // bytes per image row
+    constexpr int CPR = ROWB / 16;     // 16-byte chunks per image row
 #pragma unroll
-    for (int mi = 0; mi < TB; ++mi)
+    for (int mi = 0; mi < TB; ++mi) {
+        const int r = wm * 128 + mi * 32 + (lane & 31);  // token row of the tile
 #pragma unroll
-        for (int ni = 0; ni < NB; ++ni)
-            epilogue_block<EPI>(acc[ni][mi], acc[EPI == kSwiglu ? ni + NB : ni][mi], c, row0, row_end, n0, N, wm, wn, mi,
-                                ni, lane);
+        for (int ni = 0; ni < NB; ++ni) {
+            const floatx16& gate = acc[ni][mi];
+            const floatx16& up = acc[EPI == kSwiglu ? ni + NB : ni][mi];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                floatx4 v;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float t = acc_read(gate[4 * g + q]);
+                    if (EPI == kSwiglu) t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * acc_read(up[4 * g + q]);
+                    if (EPI == kRelu) t = fmaxf(t, 0.0f);
+                    v[q] = t;
+                }
+                // columns wn*(BNO/2) + ni*32 + 8g + 4*(lane/32) .. +3: chunk j, its lower or upper half
+                const int j = wn * (BNO / 16) + ni * 4 + g;
+                *reinterpret_cast<bf16x4*>(lds + r * ROWB + ((j ^ (r & 15)) * 16) + (lane >> 5) * 8) =
+                    __builtin_convertvector(v, bf16x4);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // one block at a time: the accumulators stay where they are until used
+        }
+    }
+    __syncthreads();
+    constexpr int RPS = 64 / CPR;  // image rows per store instruction (2 or 4)
+    const int jc = lane % CPR;
+    const int n = n0 + jc * 8;
+#pragma unroll 4
+    for (int it = 0; it < 64 / RPS; ++it) {
+        const int r = wave * 64 + it * RPS + lane / CPR;
+        const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & 15)) * 16));
+        if (row0 + r < row_end && n < N) *reinterpret_cast<uint4*>(c + (size_t)(row0 + r) * N + n) = val;
+    }
+    __syncthreads();
 }
 
 template <int EPI, bool KTAIL>
@@ -200,14 +257,14 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
     const int sk_item = xcd * per_xcd + cu;  // this workgroup's piece of the leftover tiles
 
     // lane-constant parts of the addressing
-    const int l_row = lane >> 2;
-    const int l_chunk = (lane & 3) ^ ((l_row >> 2) & 3);
+    const int l_row = lane >> 3;  // row within a load instruction's eight rows
+    const int l_pos = lane & 7;   // chunk position within the row, in LDS
     const uint32_t a_bytes = (uint32_t)(gather.perm != nullptr ? gather.rows : rows_total) * (uint32_t)K * 2u;
     const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
     const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a, a_bytes);
     const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // upper wavefronts load the W3 half
     const int f_row = lane & 31;
-    const int f_sw = (((lane >> 5) ^ ((f_row >> 2) & 3)) & 3) * 16;
+    const int f_sw = (((lane >> 5) ^ ((f_row >> 1) & 7)) & 7) * 16;
     const int x_off = (wm * 128 + f_row) * ROW_BYTES + f_sw;  // + i * 32 rows
     int w_off[WB];  // SwiGLU: weight blocks 0..WB/2-1 are gate rows, WB/2..WB-1 the matching up rows
 #pragma unroll
@@ -217,7 +274,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             rr = (i < WB / 2) ? wn * (BR / 2 / WN) + i * 32 : BR / 2 + wn * (BR / 2 / WN) + (i - WB / 2) * 32;
         else
             rr = wn * (BR / WN) + i * 32;
-        w_off[i] = TILE_BYTES + (rr + f_row) * ROW_BYTES + f_sw;
+        w_off[i] = (rr + f_row) * ROW_BYTES + f_sw;
     }
 
     for (int item = 0; item <= plan.rounds; ++item) {
@@ -241,30 +298,34 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
 
         // ---- global -> LDS -------------------------------------------------------------------------
         // Wavefront w issues, per K tile and per operand, load instructions i = 0..LPW-1; instruction
-        // (w, i) fills tile rows (LPW*w + i)*16 .. +15.  Lane l lands in row l>>2, chunk position l&3
-        // and therefore fetches global chunk (l&3) ^ ((row>>2)&3).
+        // (w, i) fills tile rows (LPW*w + i)*8 .. +7, 128 bytes each.  Lane l lands in row l>>3, chunk
+        // position l&7 and therefore fetches global chunk (l&7) ^ ((row>>1)&7).
         uint32_t a_voff[LPW], b_voff[LPW];
+        int chunk[LPW];
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int tr = (LPW * wave + i) * 16 + l_row;  // row of the tile
+            const int tr = (LPW * wave + i) * RPI + l_row;  // row of the tile
+            chunk[i] = l_pos ^ ((tr >> 1) & 7);
             int r = row0 + tr;
             r = r < row_end ? r : row_end - 1;
             if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
-            a_voff[i] = ((uint32_t)r * (uint32_t)K + l_chunk * 8) * 2u;
+            a_voff[i] = ((uint32_t)r * (uint32_t)K + chunk[i] * 8) * 2u;
             int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
             n = n < N ? n : N - 1;
-            b_voff[i] = ((uint32_t)n * (uint32_t)K + l_chunk * 8) * 2u;
+            b_voff[i] = ((uint32_t)n * (uint32_t)K + chunk[i] * 8) * 2u;
         }
         const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(wsel + (size_t)slot * N * K, b_bytes);
         const int k_tiles = ke - kb;
         const int k_first = kb * BK, k_last = (ke - 1) * BK;
-        // one load instruction: j < LPW token rows, j >= LPW weight rows, of the K tile starting at element k0
-        auto issue_load = [&](int j, int stage, int k0) {
-            const bool tok = j < LPW;
-            const int i = tok ? j : j - LPW;
+        // one load instruction i of the token (tok) or weight tile of K tile number tk, into ring slot rs.
+        // Near the end of K the tile number is clamped to the last one: the surplus lands in a slot
+        // that nobody reads any more, and the loop body stays free of branches.
+        auto issue_load = [&](bool tok, int i, int rs, int tk) {
+            int k0 = k_first + tk * BK;
+            k0 = k0 < k_last ? k0 : k_last;
             uint32_t voff = tok ? a_voff[i] : b_voff[i];
-            if (KTAIL && k0 + l_chunk * 8 >= K) voff = tok ? a_bytes : b_bytes;  // out of range: zeros
-            char* dst = lds + stage * STAGE_BYTES + (tok ? 0 : TILE_BYTES) + (LPW * wave + i) * 1024;
+            if (KTAIL && k0 + chunk[i] * 8 >= K) voff = tok ? a_bytes : b_bytes;  // out of range: zeros
+            char* dst = lds + rs * TILE_BYTES + (LPW * wave + i) * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(tok ? a_rsrc : b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 0);
         };
 
@@ -277,13 +338,15 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
         bf16x8 xf[2][TB], wf[2][WB];
-        auto load_frags = [&](int buf, int stage, int kk) {
-            const char* base = lds + stage * STAGE_BYTES;
+        // fragments of MFMA K-step kk of the tile whose token rows sit in ring slot sx and weight rows in sw
+        auto load_frags = [&](int buf, int sx, int sw, int kk) {
+            const char* xb = lds + sx * TILE_BYTES;
+            const char* wb = lds + sw * TILE_BYTES;
 #pragma unroll
             for (int i = 0; i < TB; ++i)
-                xf[buf][i] = *reinterpret_cast<const bf16x8*>(base + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
+                xf[buf][i] = *reinterpret_cast<const bf16x8*>(xb + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
 #pragma unroll
-            for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(base + (w_off[i] ^ (kk * 32)));
+            for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(wb + (w_off[i] ^ (kk * 32)));
         };
         auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -293,60 +356,73 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                     acc[ni][mi] =
                         __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
         };
-        // the step's MFMAs with its LDS reads and global->LDS loads slotted in one at a time
-        auto interleave = [&]() {
+        // the step's MFMAs with its LDS reads and `loads` global->LDS loads slotted in one at a time
+        auto interleave = [&](int loads) {
 #pragma unroll
             for (int i = 0; i < TB * WB; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                // one MFMA
-                if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
-                else if (i < TB + WB + LOADS / 2) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
+                if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one DS read
+                else if (i < TB + WB + loads) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
             }
         };
 
-        // ---- prologue: K tiles 0..2 of this piece on their way, the first landed -------------------
+        // ---- prologue: K tiles 0 and 1 of this piece on their way, the first landed ----------------
         // (every wavefront is past the last barrier of the previous trip, so nobody reads LDS any more)
+        // Ring slots: token rows of K tile t in slot 2t mod 5, weight rows in slot 2t+1 mod 5.
 #pragma unroll
-        for (int t = 0; t < STAGES - 1; ++t) {
-            const int k0 = k_first + t * BK < k_last ? k_first + t * BK : k_last;
+        for (int t = 0; t < 2; ++t) {
 #pragma unroll
-            for (int j = 0; j < LOADS; ++j) issue_load(j, t, k0);
+            for (int i = 0; i < LPW; ++i) issue_load(true, i, 2 * t, t);
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) issue_load(false, i, 2 * t + 1, t);
         }
-        barrier_keep_loads<2 * LOADS>();
-        load_frags(0, 0, 0);
+        barrier_keep_loads<2 * LPW>();
+        load_frags(0, 0, 1, 0);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- main loop -----------------------------------------------------------------------------
-        // Near the end of K the loads are clamped to the last tile: the surplus lands in a stage that
-        // nobody reads any more, and the loop body stays free of branches.
+        // Per K tile: four MFMA steps of 16.  Token rows of tile t+2 are requested during steps 0 and 1
+        // (into the slot that held the weight rows of tile t-1), weight rows of tile t+2 during step 3
+        // (into the slot of this tile's token rows, dead after the barrier).  One barrier per tile,
+        // before step 3: by then every wavefront has read its last fragments of tile t, and tile t+1
+        // has landed once only the 8 newest loads (token rows of t+2) are pending.
+        int sx = 0;  // ring slot of tile t's token rows
         for (int t = 0; t < k_tiles; ++t) {
-            const int stage = t & (STAGES - 1);
-            const int stage_in = (t + STAGES - 1) & (STAGES - 1);  // receives tile t+3; held tile t-1
-            int k3 = k_first + (t + STAGES - 1) * BK;
-            k3 = k3 < k_last ? k3 : k_last;
-            // step 0: MFMAs on the first 16 of K; second-half fragments and half of the loads issued
-            load_frags(1, stage, 1);
+            const int sw = sx + 1 >= SLOTS ? sx + 1 - SLOTS : sx + 1;   // this tile's weight rows
+            const int sx1 = sx + 2 >= SLOTS ? sx + 2 - SLOTS : sx + 2;  // next tile's token rows
+            const int sw1 = sx + 3 >= SLOTS ? sx + 3 - SLOTS : sx + 3;  // next tile's weight rows
+            const int sx2 = sx + 4 >= SLOTS ? sx + 4 - SLOTS : sx + 4;  // token rows of t+2 (held weights of t-1)
+            load_frags(1, sx, sw, 1);
 #pragma unroll
-            for (int j = 0; j < LOADS / 2; ++j) issue_load(j, stage_in, k3);
+            for (int i = 0; i < LPW / 2; ++i) issue_load(true, i, sx2, t + 2);
             mfma_step(0);
-            interleave();
+            interleave(LPW / 2);
             __builtin_amdgcn_sched_barrier(0);
-            // tile t+1 has landed once only tile t+2 (8 loads) and this step's 4 loads are pending; the
-            // LDS reads of tile t are complete: after the barrier its stage is dead, tile t+1 visible
-            barrier_keep_loads<LOADS + LOADS / 2>();
-            __builtin_amdgcn_sched_barrier(0);
-            // step 1: MFMAs on the second 16 of K; first fragments of tile t+1 and the other loads issued
-            load_frags(0, (t + 1) & (STAGES - 1), 0);
+            load_frags(0, sx, sw, 2);
 #pragma unroll
-            for (int j = LOADS / 2; j < LOADS; ++j) issue_load(j, stage_in, k3);
+            for (int i = LPW / 2; i < LPW; ++i) issue_load(true, i, sx2, t + 2);
             mfma_step(1);
-            interleave();
+            interleave(LPW / 2);
             __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, sx, sw, 3);
+            mfma_step(0);
+            interleave(0);
+            __builtin_amdgcn_sched_barrier(0);
+            barrier_keep_loads<LPW>();
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, sx1, sw1, 0);
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) issue_load(false, i, sx, t + 2);  // weight rows of t+2 over this tile's token rows
+            mfma_step(1);
+            interleave(LPW);
+            __builtin_amdgcn_sched_barrier(0);
+            sx = sx1;
         }
         // surplus loads must not land in the next trip's tiles (or outlive the workgroup's LDS)
         barrier_keep_loads<0>();
 
         if (piece < 0) {
-            epilogue<EPI>(acc, c, row0, row_end, n0, N, wm, wn, lane);
+            epilogue<EPI>(acc, c, lds, row0, row_end, n0, N, wm, wn, wave, lane);
         } else {  // a K piece of a leftover tile: raw accumulators to the workspace, [register][thread]
             float* dst = partials + kPlanFloats + (size_t)piece * (BM * BR) + tid;
 #pragma unroll
@@ -354,7 +430,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
 #pragma unroll
                 for (int j = 0; j < TB; ++j)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) dst[((i * TB + j) * 16 + v) * (64 * NW)] = acc[i][j][v];
+                    for (int v = 0; v < 16; ++v) dst[((i * TB + j) * 16 + v) * (64 * NW)] = acc_read(acc[i][j][v]);
         }
     }
 }

@@ -107,11 +107,9 @@ struct Plan {
     int splits;  // K pieces per leftover tile (1 = none)
 };
 
-__device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ offsets, int S, int n_tiles, int k_tiles, int G) {
-    int m_tiles = 0;
-    for (int s = 0; s < S; ++s) m_tiles += (offsets[s + 1] - offsets[s] + BM - 1) / BM;
+__device__ __forceinline__ Plan make_plan(int tiles, int k_tiles, int G) {
     Plan p;
-    p.tiles = m_tiles * n_tiles;
+    p.tiles = tiles;
     p.rounds = p.tiles / G;
     p.left = p.tiles - p.rounds * G;
     int sp = p.left > 0 ? G / p.left : 1;
@@ -169,6 +167,46 @@ __device__ __forceinline__ void epilogue_block(const floatx16& gate, const float
         bf16x4 o = __builtin_convertvector(v, bf16x4);
         *reinterpret_cast<bf16x4*>(crow + n) = o;
     }
+}
+
+// The slot table in registers: lane s of every wavefront holds slot s's row range and the number of
+// the first output tile of that slot, so that finding a tile's slot is one ballot and three lane
+// reads instead of a walk over slot_offsets in memory (a few thousand cycles per tile).
+struct SlotTable {
+    int begin, end;  // rows of slot `lane`
+    int tiles;       // m-tiles of slot `lane`
+    int first;       // number of the slot's first output tile (exclusive prefix of tiles * n_tiles)
+    int total;       // all output tiles (uniform)
+};
+
+__device__ __forceinline__ SlotTable make_slot_table(const int32_t* __restrict__ offsets, int S, int n_tiles, int lane) {
+    SlotTable t;
+    t.begin = lane < S ? offsets[lane] : 0;
+    t.end = lane < S ? offsets[lane + 1] : 0;
+    t.tiles = (t.end - t.begin + BM - 1) / BM;
+    const int span = t.tiles * n_tiles;
+    int incl = span;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    t.first = incl - span;
+    t.total = __builtin_amdgcn_readlane(incl, 63);
+    return t;
+}
+
+__device__ __forceinline__ void decode_tile(const SlotTable& t, int S, int lane, int L, int& slot, int& row0,
+                                            int& row_end, int& nt) {
+    // slots are in tile order and an empty slot starts where its successor does: the last slot that
+    // starts at or before L is the non-empty one that holds it
+    const unsigned long long m = __ballot(lane < S && t.first <= L);
+    slot = __popcll(m) - 1;
+    const int rem = L - __builtin_amdgcn_readlane(t.first, slot);
+    const int tiles = __builtin_amdgcn_readlane(t.tiles, slot);
+    nt = rem / tiles;
+    row0 = __builtin_amdgcn_readlane(t.begin, slot) + (rem % tiles) * BM;
+    row_end = __builtin_amdgcn_readlane(t.end, slot);
 }
 
 // Reads one accumulator where it lives (an AGPR).  Written out as an instruction so that the compiler
@@ -249,7 +287,8 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
     const int wm = wave / WN, wn = wave % WN;
     const int k_tiles_all = (K + BK - 1) / BK;
     const int G = gridDim.x;
-    const Plan plan = make_plan(offsets, S, n_tiles, k_tiles_all, G);
+    const SlotTable table = make_slot_table(offsets, S, n_tiles, lane);
+    const Plan plan = make_plan(table.total, k_tiles_all, G);
     if (blockIdx.x == 0 && tid == 0)  // for the fix-up kernel, which then need not derive it again
         *reinterpret_cast<int4*>(partials) = make_int4(plan.tiles, plan.rounds, plan.left, plan.splits);
     const int rows_total = offsets[S];
@@ -293,7 +332,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             }
         }
         int slot, row0, row_end, nt;
-        decode_tile(offsets, S, n_tiles, L, slot, row0, row_end, nt);
+        decode_tile(table, S, lane, L, slot, row0, row_end, nt);
         const int n0 = nt * BNO;
 
         // ---- global -> LDS -------------------------------------------------------------------------
@@ -318,13 +357,14 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         const int k_tiles = ke - kb;
         const int k_first = kb * BK, k_last = (ke - 1) * BK;
         // one load instruction i of the token (tok) or weight tile of K tile number tk, into ring slot rs.
-        // Near the end of K the tile number is clamped to the last one: the surplus lands in a slot
-        // that nobody reads any more, and the loop body stays free of branches.
+        // Near the end of K the loads go on (the loop body stays free of branches) but out of range:
+        // zeros land in a slot that nobody reads any more.
         auto issue_load = [&](bool tok, int i, int rs, int tk) {
             int k0 = k_first + tk * BK;
             k0 = k0 < k_last ? k0 : k_last;
             uint32_t voff = tok ? a_voff[i] : b_voff[i];
-            if (KTAIL && k0 + chunk[i] * 8 >= K) voff = tok ? a_bytes : b_bytes;  // out of range: zeros
+            // out of range (zeros arrive, memory is not touched): chunks past K, and the loads past the last tile
+            if ((KTAIL && k0 + chunk[i] * 8 >= K) || tk >= k_tiles) voff = tok ? a_bytes : b_bytes;
             char* dst = lds + rs * TILE_BYTES + (LPW * wave + i) * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(tok ? a_rsrc : b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 0);
         };

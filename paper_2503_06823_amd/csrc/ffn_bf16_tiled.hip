@@ -40,6 +40,8 @@
 // ids are remapped: the workgroups of an XCD hold consecutive tiles of the (slot, n-tile, m-tile)
 // order with the m-tile fastest, which keeps one weight panel (and the slot's token panels) in
 // that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace emoe {
@@ -346,9 +348,10 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             const int tr = (LPW * wave + i) * RPI + l_row;  // row of the tile
             chunk[i] = l_pos ^ ((tr >> 1) & 7);
             int r = row0 + tr;
-            r = r < row_end ? r : row_end - 1;
+            const bool past = r >= row_end;  // rows past the slot's end: out of range, zeros without memory traffic
+            r = past ? row_end - 1 : r;
             if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
-            a_voff[i] = ((uint32_t)r * (uint32_t)K + chunk[i] * 8) * 2u;
+            a_voff[i] = past ? a_bytes : ((uint32_t)r * (uint32_t)K + chunk[i] * 8) * 2u;
             int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
             n = n < N ? n : N - 1;
             b_voff[i] = ((uint32_t)n * (uint32_t)K + chunk[i] * 8) * 2u;
@@ -426,38 +429,54 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // (into the slot of this tile's token rows, dead after the barrier).  One barrier per tile,
         // before step 3: by then every wavefront has read its last fragments of tile t, and tile t+1
         // has landed once only the 8 newest loads (token rows of t+2) are pending.
-        int sx = 0;  // ring slot of tile t's token rows
-        for (int t = 0; t < k_tiles; ++t) {
-            const int sw = sx + 1 >= SLOTS ? sx + 1 - SLOTS : sx + 1;   // this tile's weight rows
-            const int sx1 = sx + 2 >= SLOTS ? sx + 2 - SLOTS : sx + 2;  // next tile's token rows
-            const int sw1 = sx + 3 >= SLOTS ? sx + 3 - SLOTS : sx + 3;  // next tile's weight rows
-            const int sx2 = sx + 4 >= SLOTS ? sx + 4 - SLOTS : sx + 4;  // token rows of t+2 (held weights of t-1)
-            load_frags(1, sx, sw, 1);
+        // A wavefront whose 128 token rows all lie past the slot's end (a ragged last tile) takes part
+        // in the loads and barriers but skips its fragment reads and MFMAs: the kernel runs at the
+        // chip's power limit, so work not done is speed for the others.
+        auto k_loop = [&](auto idle_tag) {
+            constexpr bool IDLE = decltype(idle_tag)::value;
+            int sx = 0;  // ring slot of tile t's token rows
+            for (int t = 0; t < k_tiles; ++t) {
+                const int sw = sx + 1 >= SLOTS ? sx + 1 - SLOTS : sx + 1;   // this tile's weight rows
+                const int sx1 = sx + 2 >= SLOTS ? sx + 2 - SLOTS : sx + 2;  // next tile's token rows
+                const int sw1 = sx + 3 >= SLOTS ? sx + 3 - SLOTS : sx + 3;  // next tile's weight rows
+                const int sx2 = sx + 4 >= SLOTS ? sx + 4 - SLOTS : sx + 4;  // token rows of t+2 (held weights of t-1)
+                if (!IDLE) load_frags(1, sx, sw, 1);
 #pragma unroll
-            for (int i = 0; i < LPW / 2; ++i) issue_load(true, i, sx2, t + 2);
-            mfma_step(0);
-            interleave(LPW / 2);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, sx, sw, 2);
+                for (int i = 0; i < LPW / 2; ++i) issue_load(true, i, sx2, t + 2);
+                if (!IDLE) {
+                    mfma_step(0);
+                    interleave(LPW / 2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (!IDLE) load_frags(0, sx, sw, 2);
 #pragma unroll
-            for (int i = LPW / 2; i < LPW; ++i) issue_load(true, i, sx2, t + 2);
-            mfma_step(1);
-            interleave(LPW / 2);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, sx, sw, 3);
-            mfma_step(0);
-            interleave(0);
-            __builtin_amdgcn_sched_barrier(0);
-            barrier_keep_loads<LPW>();
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, sx1, sw1, 0);
+                for (int i = LPW / 2; i < LPW; ++i) issue_load(true, i, sx2, t + 2);
+                if (!IDLE) {
+                    mfma_step(1);
+                    interleave(LPW / 2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (!IDLE) {
+                    load_frags(1, sx, sw, 3);
+                    mfma_step(0);
+                    interleave(0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                barrier_keep_loads<LPW>();
+                __builtin_amdgcn_sched_barrier(0);
+                if (!IDLE) load_frags(0, sx1, sw1, 0);
 #pragma unroll
-            for (int i = 0; i < LPW; ++i) issue_load(false, i, sx, t + 2);  // weight rows of t+2 over this tile's token rows
-            mfma_step(1);
-            interleave(LPW);
-            __builtin_amdgcn_sched_barrier(0);
-            sx = sx1;
-        }
+                for (int i = 0; i < LPW; ++i) issue_load(false, i, sx, t + 2);  // weight rows of t+2 over this tile's token rows
+                if (!IDLE) {
+                    mfma_step(1);
+                    interleave(LPW);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                sx = sx1;
+            }
+        };
+        if (row0 + wm * 128 >= row_end) k_loop(std::true_type{});
+        else k_loop(std::false_type{});
         // surplus loads must not land in the next trip's tiles (or outlive the workgroup's LDS)
         barrier_keep_loads<0>();
 

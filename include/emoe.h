@@ -288,6 +288,50 @@ int emoe_loader_layer_end(emoe_loader *loader, int32_t layer, void *compute_stre
 int emoe_loader_residents(const emoe_loader *loader, int32_t layer, int32_t *expert_of_slot_host);
 int emoe_loader_synchronize(emoe_loader *loader);
 
+/*
+ * Request scheduler (Section 3.5).  Host-only, no GPU needed.
+ *
+ * emoe_request: input_tokens = W of the request; slo = its latency SLO;
+ * first_token_slo = how soon its first token is due (the stringency the waiting
+ * queue is ordered by); run_time = r_i so far; g_remaining = G_i, tokens it
+ * still has to generate (the task's profiled length when scheduled); g_initial
+ * = that profiled length; delta_e = expert loading latency that scheduling this
+ * request causes (profiled; 0 for a task no layer is sensitive to).
+ *
+ * emoe_expected_latency: Eq. 3 for running request i,
+ *   t_i = dE + (W + n_i * G_i) * c + r_i,
+ * n_i = running requests other than i with more tokens left than i; dE and W
+ * from new_request, or 0 if new_request is NULL (the latency as things stand).
+ *
+ * emoe_schedule: Algorithm 1.  The waiting requests are tried in ascending
+ * first_token_slo (equal values in queue order).  A request is admitted if its
+ * input tokens plus those held by the scheduled requests stay below t_max, and
+ * every running request whose expected latency is below its SLO now keeps it
+ * below its SLO with the new request (Eq. 3).  An admitted request joins the
+ * running ones (run_time 0) for the candidates after it.  admitted [n_waiting]
+ * out: indices into `waiting` in admission order; *n_admitted their number.
+ *
+ * emoe_generation_tick: after one iteration of token generation G_i is
+ * decremented; if it reaches 0 and the request has not completed it is reset
+ * to reset_fraction (the paper's example: 0.05) of g_initial, at least 1.
+ */
+typedef struct {
+    int32_t input_tokens;
+    int32_t g_remaining;
+    int32_t g_initial;
+    int32_t reserved;
+    double slo;
+    double first_token_slo;
+    double run_time;
+    double delta_e;
+} emoe_request;
+
+int emoe_expected_latency(int32_t n_running, const emoe_request *running, int32_t i, double c,
+                          const emoe_request *new_request, double *latency);
+int emoe_schedule(int32_t n_waiting, const emoe_request *waiting, int32_t n_scheduled,
+                  const emoe_request *scheduled, int64_t t_max, double c, int32_t *admitted, int32_t *n_admitted);
+int emoe_generation_tick(emoe_request *request, int32_t completed, double reset_fraction);
+
 #ifdef __cplusplus
 }
 #endif

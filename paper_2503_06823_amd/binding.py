@@ -26,7 +26,8 @@ EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_rou
            "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_combine", "emoe_load_experts", "emoe_expected_tokens",
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
-           "emoe_loader_residents", "emoe_loader_synchronize")
+           "emoe_loader_residents", "emoe_loader_synchronize", "emoe_expected_latency", "emoe_schedule",
+           "emoe_generation_tick")
 
 
 class EmoeLayerDesc(ctypes.Structure):
@@ -324,3 +325,44 @@ class Loader:
             self.close()
         except Exception:
             pass
+
+
+class EmoeRequest(ctypes.Structure):
+    _fields_ = [("input_tokens", ctypes.c_int32), ("g_remaining", ctypes.c_int32), ("g_initial", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("slo", ctypes.c_double), ("first_token_slo", ctypes.c_double),
+                ("run_time", ctypes.c_double), ("delta_e", ctypes.c_double)]
+
+
+def make_request(input_tokens, slo, first_token_slo, run_time=0.0, g_remaining=0, g_initial=0, delta_e=0.0) -> EmoeRequest:
+    return EmoeRequest(int(input_tokens), int(g_remaining), int(g_initial), 0, float(slo), float(first_token_slo),
+                       float(run_time), float(delta_e))
+
+
+def _request_array(requests):
+    requests = list(requests)
+    return (EmoeRequest * max(len(requests), 1))(*requests), len(requests)
+
+
+def emoe_expected_latency(running, i, c, new_request=None, check=True):
+    arr, n = _request_array(running)
+    out = ctypes.c_double(0.0)
+    new = ctypes.byref(new_request) if new_request is not None else None
+    rc = lib().emoe_expected_latency(n, arr, int(i), ctypes.c_double(c), new, ctypes.byref(out))
+    _check(rc, "emoe_expected_latency", check)
+    return out.value if rc == EMOE_OK else rc
+
+
+def emoe_schedule(waiting, scheduled, t_max, c, check=True):
+    """Indices of the admitted waiting requests, in admission order (or the status)."""
+    w, nw = _request_array(waiting)
+    s, ns = _request_array(scheduled)
+    out = (ctypes.c_int32 * max(nw, 1))()
+    n = ctypes.c_int32(0)
+    rc = lib().emoe_schedule(nw, w, ns, s, ctypes.c_int64(int(t_max)), ctypes.c_double(c), out, ctypes.byref(n))
+    _check(rc, "emoe_schedule", check)
+    return list(out)[:n.value] if rc == EMOE_OK else rc
+
+
+def emoe_generation_tick(request: EmoeRequest, completed: bool, reset_fraction: float = 0.05, check=True) -> int:
+    rc = lib().emoe_generation_tick(ctypes.byref(request), 1 if completed else 0, ctypes.c_double(reset_fraction))
+    return _check(rc, "emoe_generation_tick", check)

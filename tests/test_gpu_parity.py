@@ -31,11 +31,11 @@ SMALL_CASES = [
     # few output tiles and a long K: leftover tiles are split along K into pieces (with a K tail in both passes)
     cfg("tiled_splitk_ktail", T=600, d_model=1032, d_ff=1160, E=8, k=2, R=4, S=6, index=58),
     cfg("tiled_topk6", T=600, d_model=256, d_ff=384, E=64, k=6, R=24, zipf_s=1.2, resident="popular", index=46),
-    # streaming path (A <= 48 S): few rows per slot, slots with 0 rows, a slot with > 64 rows
+    # streaming path (A <= 28 S): few rows per slot, slots with 0 rows, a slot with > 64 rows
     cfg("stream_decode", T=64, d_model=512, d_ff=1088, E=8, k=2, R=6, index=47),
     cfg("stream_ktail", T=20, d_model=200, d_ff=328, E=8, k=2, R=5, S=8, index=48),
-    cfg("stream_relu_hot_slot", act="relu", T=90, d_model=256, d_ff=384, E=4, k=1, R=2, zipf_s=3.0, index=49),
-    cfg("stream_two_token_blocks", T=80, d_model=128, d_ff=192, E=4, k=1, R=2, index=57),
+    cfg("stream_relu_hot_slot", act="relu", T=90, d_model=256, d_ff=384, E=4, k=1, R=2, S=4, zipf_s=3.0, index=49),
+    cfg("stream_two_token_blocks", T=80, d_model=128, d_ff=192, E=4, k=1, R=2, S=4, index=57),
     cfg("stream_k_equals_R", T=9, d_model=128, d_ff=192, E=6, k=3, R=3, index=50),
     cfg("single_token", T=1, d_model=128, d_ff=256, E=8, k=2, R=4, index=51),
     cfg("single_expert_dense", T=300, d_model=128, d_ff=256, E=1, k=1, R=1, index=52),

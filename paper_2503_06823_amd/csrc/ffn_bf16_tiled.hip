@@ -37,9 +37,9 @@
 // Ragged groups: group sizes live on the device.  The launch is persistent (one workgroup per CU);
 // every workgroup derives the list of (slot, m-tile, n-tile) tiles from slot_offsets and takes its
 // share (see "work distribution" below).  Workgroup ids are dealt round-robin to the 8 XCDs, so
-// ids are remapped: the workgroups of an XCD hold consecutive tiles of the (slot, n-tile, m-tile)
-// order with the m-tile fastest, which keeps one weight panel (and the slot's token panels) in
-// that XCD's L2.
+// ids are remapped: the workgroups of an XCD hold consecutive tiles of an order in which 32
+// consecutive tiles form a block of 8 m-tiles x 4 n-tiles of one slot (see tile_in_slot), so that
+// XCD's L2 supplies 12 operand panels for 32 tiles.
 #include <type_traits>
 
 #include "common.h"
@@ -96,7 +96,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // ---- work distribution ------------------------------------------------------------------------
 // The launch is persistent: one workgroup per CU.  Output tiles are numbered in (slot, n-tile,
-// m-tile) order, m fastest.  The first `rounds * G` tiles are dealt out whole, `rounds` per
+// m-tile) order of tile_in_slot.  The first `rounds * G` tiles are dealt out whole, `rounds` per
 // workgroup, so that the 32 workgroups of an XCD hold 32 consecutive tiles at any time (one weight
 // panel and the slot's token panels stay in that XCD's L2).  The `left` tiles that do not fill a
 // round are split along K into `splits` pieces each, so that they too occupy (nearly) every CU: a
@@ -122,6 +122,31 @@ __device__ __forceinline__ Plan make_plan(int tiles, int k_tiles, int G) {
     return p;
 }
 
+// Order of a slot's m_tiles x n_tiles output tiles.  The 32 workgroups of an XCD hold 32 consecutive
+// tiles at any time and their L2 has to supply one operand panel per distinct m-tile and per
+// distinct n-tile among them, so consecutive tiles should form compact blocks: the n-tiles are
+// taken four at a time, and inside such a group of columns the m-tiles eight at a time, m fastest
+// (12 panels for 32 tiles; m fastest over a whole tall slot would need up to 33).
+// rem = number of the tile within the slot -> its m-tile and n-tile.
+constexpr int kBlockM = 8, kBlockN = 4;
+__device__ __forceinline__ void tile_in_slot(int rem, int m_tiles, int n_tiles, int& mt, int& nt) {
+    const int group = rem / (m_tiles * kBlockN);  // group of up to four n-tiles
+    const int gn = n_tiles - group * kBlockN < kBlockN ? n_tiles - group * kBlockN : kBlockN;
+    int r = rem - group * (m_tiles * kBlockN);
+    const int full = m_tiles / kBlockM;           // whole blocks of eight m-tiles
+    int mb = kBlockM, m0 = 0;
+    if (r < full * kBlockM * gn) {
+        m0 = (r / (kBlockM * gn)) * kBlockM;
+        r %= kBlockM * gn;
+    } else {
+        r -= full * kBlockM * gn;
+        m0 = full * kBlockM;
+        mb = m_tiles - m0;
+    }
+    mt = m0 + r % mb;
+    nt = group * kBlockN + r / mb;
+}
+
 // tile number -> slot, first row, end of the slot's rows, n-tile
 __device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets, int S, int n_tiles, int L, int& slot,
                                             int& row0, int& row_end, int& nt) {
@@ -133,8 +158,9 @@ __device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets,
         const int span = tiles * n_tiles;
         if (rem < span) {
             slot = s;
-            nt = rem / tiles;
-            row0 = b + (rem % tiles) * BM;
+            int mt;
+            tile_in_slot(rem, tiles, n_tiles, mt, nt);
+            row0 = b + mt * BM;
             row_end = e;
             return;
         }
@@ -198,16 +224,17 @@ __device__ __forceinline__ SlotTable make_slot_table(const int32_t* __restrict__
     return t;
 }
 
-__device__ __forceinline__ void decode_tile(const SlotTable& t, int S, int lane, int L, int& slot, int& row0,
-                                            int& row_end, int& nt) {
+__device__ __forceinline__ void decode_tile(const SlotTable& t, int S, int n_tiles, int lane, int L, int& slot,
+                                            int& row0, int& row_end, int& nt) {
     // slots are in tile order and an empty slot starts where its successor does: the last slot that
     // starts at or before L is the non-empty one that holds it
     const unsigned long long m = __ballot(lane < S && t.first <= L);
     slot = __popcll(m) - 1;
     const int rem = L - __builtin_amdgcn_readlane(t.first, slot);
     const int tiles = __builtin_amdgcn_readlane(t.tiles, slot);
-    nt = rem / tiles;
-    row0 = __builtin_amdgcn_readlane(t.begin, slot) + (rem % tiles) * BM;
+    int mt;
+    tile_in_slot(rem, tiles, n_tiles, mt, nt);
+    row0 = __builtin_amdgcn_readlane(t.begin, slot) + mt * BM;
     row_end = __builtin_amdgcn_readlane(t.end, slot);
 }
 
@@ -334,7 +361,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             }
         }
         int slot, row0, row_end, nt;
-        decode_tile(table, S, lane, L, slot, row0, row_end, nt);
+        decode_tile(table, S, n_tiles, lane, L, slot, row0, row_end, nt);
         const int n0 = nt * BNO;
 
         // ---- global -> LDS -------------------------------------------------------------------------

@@ -24,6 +24,8 @@ int validate_desc(const emoe_layer_desc* d) {
     // 32-bit byte offsets into the activation buffers, with room for one more row past the end (the
     // kernels address "out of range" as buffer size + an offset within a row)
     if ((A + 2) * widest > (1ll << 31)) return EMOE_ERR_SHAPE;
+    // and into one slot's weight matrix
+    if ((long long)d->d_model * d->d_ff >= (1ll << 31)) return EMOE_ERR_SHAPE;
     return EMOE_OK;
 }
 
@@ -36,26 +38,31 @@ PermuteWs permute_ws_layout(const emoe_layer_desc& d) {
     return w;
 }
 
-bool ffn_use_stream_path(const emoe_layer_desc& d);
-
 FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
     FfnWs w;
     const size_t A = (size_t)d.T * d.k;
     w.h = 0;
     w.partials = align256((A > 0 ? A : 1) * d.d_ff * elem_bytes(d));
     w.total = w.partials;
-    if (d.dtype == EMOE_BF16 && !ffn_use_stream_path(d)) w.total += kTiledPartialBytes;
+    if (d.dtype == EMOE_BF16 && ffn_bf16_path(d) == kFfnTiled) w.total += kTiledPartialBytes;
     return w;
 }
 
+// Row counts live on the device, so the choice goes by the average number of rows per slot.
 // Few rows per slot: reading the weights dominates, use the streaming kernels.  They take 32 rows
 // of a slot per pass over its weights, so they win only while (nearly) every slot fits one pass:
 // at the Mixtral shape 369 us against the tiled kernels' 477 us with 21 rows per slot, but 661 us
-// against 477 us with 42.  Row counts live on the device, so the switch goes by the average;
-// random routing at 28 rows per slot on average puts about one slot in five over 32 rows.
-bool ffn_use_stream_path(const emoe_layer_desc& d) {
+// against 477 us with 42; random routing at 28 rows per slot on average puts about one slot in
+// five over 32 rows.  Up to kMidRowsPerSlot rows per slot the tiles of 128 token rows are used:
+// they keep more weight bytes in flight (Mixtral shape, 64 rows per slot: 578 us against 608 us), but
+// lose once many slots need a second tile (124 rows per slot: 668 against 632 us).
+constexpr long long kStreamRowsPerSlot = 28;
+constexpr long long kMidRowsPerSlot = 100;
+FfnPath ffn_bf16_path(const emoe_layer_desc& d) {
     const long long A = (long long)d.T * d.k;
-    return A <= 28ll * d.S;
+    if (A <= kStreamRowsPerSlot * d.S) return kFfnStream;
+    if (A <= kMidRowsPerSlot * d.S) return kFfnMid;
+    return kFfnTiled;
 }
 
 }  // namespace emoe
@@ -143,8 +150,10 @@ static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void
     hipError_t e;
     if (desc->dtype == EMOE_F32)
         e = launch_ffn_f32(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
-    else if (ffn_use_stream_path(*desc))
+    else if (ffn_bf16_path(*desc) == kFfnStream)
         e = launch_ffn_bf16_stream(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
+    else if (ffn_bf16_path(*desc) == kFfnMid)
+        e = launch_ffn_bf16_mid(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
     else
         e = launch_ffn_bf16_tiled(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
     return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;

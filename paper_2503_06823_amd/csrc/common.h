@@ -44,8 +44,10 @@ constexpr int kPermuteChunk = 1024;  // assignments per workgroup in the countin
 PermuteWs permute_ws_layout(const emoe_layer_desc& d);
 FfnWs ffn_ws_layout(const emoe_layer_desc& d);
 
-// True when the FFN runs the weight-streaming (small batch) kernels instead of the tiled GEMM.
-bool ffn_use_stream_path(const emoe_layer_desc& d);
+// Which kernels the bf16 FFN runs: weight streaming (few rows per slot), tiles of 128 token rows
+// (up to a few hundred rows per slot) or tiles of 256 token rows.
+enum FfnPath { kFfnStream = 0, kFfnMid = 1, kFfnTiled = 2 };
+FfnPath ffn_bf16_path(const emoe_layer_desc& d);
 
 // Host-side checks common to the entry points; returns EMOE_OK or an error.
 int validate_desc(const emoe_layer_desc* d);
@@ -77,6 +79,9 @@ hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, RowGathe
 hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets,
                                  const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                  int passes, hipStream_t st);
+hipError_t launch_ffn_bf16_mid(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets,
+                               const void* w1, const void* w3, const void* w2, void* y_perm, void* ws, int passes,
+                               hipStream_t st);
 hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets,
                                   const void* w1, const void* w3, const void* w2, void* y_perm, void* ws,
                                   int passes, hipStream_t st);

@@ -1,0 +1,369 @@
+// Expert FFN for bf16 layers with a few dozen to a few hundred rows per slot: a prompt or two in
+// prefill, a large decode batch (eMoE Section 5.5 measures prompts of 512 tokens, which leaves
+// 128 rows per expert at top-2 of 8).  In this range the layer is bound by reading the resident
+// experts' weights (Section 5.1: fewer experts, fewer global-memory reads) or sits near the ridge
+// between that and the matrix cores, and tiles of 256 token rows waste both: a slot of 130 rows
+// fills half a tile, a slot of 260 rows takes two.
+//
+//   pass 1: h[r, n]      = act(x_perm[r,:] . W1_s[n,:]) (* x_perm[r,:] . W3_s[n,:])   K = d_model
+//   pass 2: y_perm[r, n] = h[r,:] . W2_s[n,:]                                         K = d_ff
+//
+// Tile: 128 token rows x 256 weight rows per workgroup (SwiGLU: 128 rows of W1 and the same 128 of
+// W3, so the activation is applied in registers); four wavefronts (2 x 2), each 64 tokens x 128
+// weight rows = 2 x 4 blocks of v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The weight rows are
+// the MFMA's row operand, so a lane ends up with four consecutive output columns of one token.
+//
+// Data movement: K is walked in tiles of 64 (a tile row = one 128-byte line).  A stage of LDS holds
+// the token rows (16 KiB) and the weight rows (32 KiB) of one K tile; both go from global memory
+// straight into LDS (buffer_load_dwordx4 ... lds, 1 KiB per instruction, eight rows of 128 bytes).
+// Three stages: while tile t is multiplied, tiles t+1 and t+2 are on their way, 64 KiB of weights
+// in flight per CU, which is what it takes to keep HBM busy at its latency.  The narrow token tile
+// is what buys the third stage: with 256 token rows only two and a half stages fit.
+// The 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), chosen by which global
+// chunk a lane fetches, so the MFMA fragment reads (32 rows x one chunk) have no bank conflicts.
+// Chunks past K (when K is not a multiple of 64), rows past the slot's end and weight rows past N
+// are addressed out of range of their buffer: zeros arrive and no memory is touched.
+//
+// One workgroup per output tile, not persistent: tiles are short here (at most 64 K tiles of half
+// the work of the large kernel's) and the hardware's dispatcher balances them.  Group sizes live on
+// the device: the launch covers an upper bound of tiles and surplus workgroups exit.  Tiles are
+// numbered slot by slot, and inside a slot all m-tiles of an n-tile are consecutive; workgroup ids
+// go round-robin over the 8 XCDs, so ids are remapped so that an XCD works on consecutive tiles:
+// the m-tiles that share a weight panel run at the same time behind the same L2, and the panel is
+// fetched from HBM once.
+#include <type_traits>
+
+#include "common.h"
+
+namespace emoe {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr int BM = 128;                    // token rows per tile
+constexpr int BR = 256;                    // weight rows per tile (SwiGLU: 128 of W1 + 128 of W3)
+constexpr int BK = 64;                     // K elements per tile
+constexpr int ROW_BYTES = BK * 2;          // 128
+constexpr int X_TILE = BM * ROW_BYTES;     // 16 KiB
+constexpr int W_TILE = BR * ROW_BYTES;     // 32 KiB
+constexpr int STAGE_BYTES = X_TILE + W_TILE;
+constexpr int STAGES = 3;
+constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;  // 144 KiB
+constexpr int NW = 4;                      // wavefronts: 2 (tokens) x 2 (weight rows)
+constexpr int TB = 2;                      // 32-token blocks per wavefront
+constexpr int WB = 4;                      // 32-row weight blocks per wavefront
+constexpr int LX = BM / 8 / NW;            // token load instructions per wavefront and K tile (4)
+constexpr int LW = BR / 8 / NW;            // weight load instructions per wavefront and K tile (8)
+constexpr int XCDS = 8;
+
+enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
+
+// s_waitcnt immediate: vmcnt <= n, all LDS traffic done (vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int wait_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0x0 << 8); }
+
+// Workgroup barrier that leaves up to N of this wavefront's global->LDS loads pending (loads retire
+// in order, so "at most N pending" means everything older has landed) and waits for its LDS reads.
+template <int N>
+__device__ __forceinline__ void barrier_keep_loads() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(wait_imm(N));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int EPI, bool KTAIL>
+__global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
+                                                     const int32_t* __restrict__ offsets,
+                                                     const bf16_t* __restrict__ b0, const bf16_t* __restrict__ b1,
+                                                     bf16_t* __restrict__ c, int S, int N, int K, int n_tiles) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
+    constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;   // output column blocks per wavefront
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- which tile: lane s holds slot s's rows and the number of its first tile ------------------
+    const int s_begin = lane < S ? offsets[lane] : 0;
+    const int s_end = lane < S ? offsets[lane + 1] : 0;
+    const int s_mtiles = (s_end - s_begin + BM - 1) / BM;
+    const int span = s_mtiles * n_tiles;
+    int incl = span;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    const int first = incl - span;
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    const int per_xcd = (total + XCDS - 1) / XCDS;
+    const int xcd = blockIdx.x % XCDS, idx = blockIdx.x / XCDS;
+    const int L = xcd * per_xcd + idx;
+    if (idx >= per_xcd || L >= total) return;
+    // an empty slot starts where its successor does: the last slot that starts at or before L holds it
+    const int slot = __popcll(__ballot(lane < S && first <= L)) - 1;
+    const int rem = L - __builtin_amdgcn_readlane(first, slot);
+    const int mtiles = __builtin_amdgcn_readlane(s_mtiles, slot);
+    const int mt = rem % mtiles, nt = rem / mtiles;
+    const int row0 = __builtin_amdgcn_readlane(s_begin, slot) + mt * BM;
+    const int row_end = __builtin_amdgcn_readlane(s_end, slot);
+    const int n0 = nt * BNO;
+    const int rows_total = offsets[S];
+
+    // ---- global -> LDS addressing --------------------------------------------------------------------
+    // Load instruction (w, i) of an operand fills tile rows (L? * w + i) * 8 .. +7; lane l lands in row
+    // l >> 3 of those, chunk position l & 7, and therefore fetches global chunk (l & 7) ^ ((row >> 1) & 7).
+    const int l_row = lane >> 3, l_pos = lane & 7;
+    const uint32_t a_bytes = (uint32_t)(gather.perm != nullptr ? gather.rows : rows_total) * (uint32_t)K * 2u;
+    const uint32_t b_bytes = (uint32_t)N * (uint32_t)K * 2u;
+    uint32_t x_voff[LX], w_voff[LW];
+    int x_chunk[LX], w_chunk[LW];
+#pragma unroll
+    for (int i = 0; i < LX; ++i) {
+        const int tr = (LX * wave + i) * 8 + l_row;
+        x_chunk[i] = l_pos ^ ((tr >> 1) & 7);
+        int r = row0 + tr;
+        const bool past = r >= row_end;
+        r = past ? row_end - 1 : r;
+        if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
+        x_voff[i] = past ? a_bytes : ((uint32_t)r * (uint32_t)K + x_chunk[i] * 8) * 2u;
+    }
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const int tr = (LW * wave + i) * 8 + l_row;
+        w_chunk[i] = l_pos ^ ((tr >> 1) & 7);
+        const int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: rows 128..255 = the same rows of W3
+        w_voff[i] = n >= N ? b_bytes : ((uint32_t)n * (uint32_t)K + w_chunk[i] * 8) * 2u;
+    }
+    const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // wavefronts 2, 3 load the W3 half
+    const __amdgpu_buffer_rsrc_t a_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a), 0, (int)a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(wsel + (size_t)slot * N * K), 0, (int)b_bytes, 0x00020000);
+    const int k_tiles = (K + BK - 1) / BK;
+    const int k_last = (k_tiles - 1) * BK;
+    // K tile number tk into stage st.  Past the last tile the loads go on (no branches in the loop)
+    // but out of range: zeros land in a stage that nobody reads any more.
+    auto issue_x = [&](int i, int st, int tk) {
+        int k0 = tk * BK;
+        k0 = k0 < k_last ? k0 : k_last;
+        uint32_t v = x_voff[i];
+        if ((KTAIL && k0 + x_chunk[i] * 8 >= K) || tk >= k_tiles) v = a_bytes;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void*)(lds + st * STAGE_BYTES + (LX * wave + i) * 1024), 16,
+                                                 (int)v, k0 * 2, 0, 0);
+    };
+    auto issue_w = [&](int i, int st, int tk) {
+        int k0 = tk * BK;
+        k0 = k0 < k_last ? k0 : k_last;
+        uint32_t v = w_voff[i];
+        if ((KTAIL && k0 + w_chunk[i] * 8 >= K) || tk >= k_tiles) v = b_bytes;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc,
+                                                 (lds_void*)(lds + st * STAGE_BYTES + X_TILE + (LW * wave + i) * 1024), 16,
+                                                 (int)v, k0 * 2, 0, 0);
+    };
+    auto issue_tile = [&](int st, int tk) {
+#pragma unroll
+        for (int i = 0; i < LX; ++i) issue_x(i, st, tk);
+#pragma unroll
+        for (int i = 0; i < LW; ++i) issue_w(i, st, tk);
+    };
+
+    // ---- fragments: lane holds row lane % 32 and, in MFMA K-step kk, chunk 2 kk + lane / 32 ---------
+    const int f_row = lane & 31;
+    const int f_sw = (((lane >> 5) ^ ((f_row >> 1) & 7)) & 7) * 16;
+    const int x_off = (wm * 64 + f_row) * ROW_BYTES + f_sw;  // + 32 rows per token block
+    int w_off[WB];  // SwiGLU: blocks 0, 1 are gate rows, blocks 2, 3 the matching up rows
+#pragma unroll
+    for (int i = 0; i < WB; ++i) {
+        int rr;
+        if (EPI == kSwiglu) rr = (i < WB / 2) ? wn * 64 + i * 32 : BR / 2 + wn * 64 + (i - WB / 2) * 32;
+        else rr = wn * 128 + i * 32;
+        w_off[i] = X_TILE + (rr + f_row) * ROW_BYTES + f_sw;
+    }
+
+    floatx16 acc[WB][TB];
+#pragma unroll
+    for (int i = 0; i < WB; ++i)
+#pragma unroll
+        for (int j = 0; j < TB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    bf16x8 xf[2][TB], wf[2][WB];
+    auto load_frags = [&](int buf, int st, int kk) {
+        const char* base = lds + st * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < TB; ++i)
+            xf[buf][i] = *reinterpret_cast<const bf16x8*>(base + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
+#pragma unroll
+        for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(base + (w_off[i] ^ (kk * 32)));
+    };
+    auto mfma_step = [&](int buf) {
+#pragma unroll
+        for (int ni = 0; ni < WB; ++ni)
+#pragma unroll
+            for (int mi = 0; mi < TB; ++mi)
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
+    };
+    // a step's eight MFMAs with its six fragment reads and (in the step after the barrier) the twelve
+    // global->LDS loads slotted between them, so that no memory instruction queues up behind another
+    auto interleave = [&](auto with_loads) {
+        constexpr bool LOADS = decltype(with_loads)::value;
+#pragma unroll
+        for (int i = 0; i < TB * WB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
+            if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one LDS read
+            if (LOADS) __builtin_amdgcn_sched_group_barrier(0x010, (LX + LW + TB * WB - 1) / (TB * WB), 0);  // VMEM
+        }
+    };
+
+    // ---- prologue: tiles 0, 1 and 2 on their way, tile 0 landed, its first fragments read -----------
+    issue_tile(0, 0);
+    issue_tile(1, 1);
+    issue_tile(2, 2);
+    barrier_keep_loads<2 * (LX + LW)>();
+    load_frags(0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- main loop -------------------------------------------------------------------------------------
+    // Per K tile four MFMA steps of 16.  The barrier comes before the last step: by then every wavefront
+    // holds its last fragments of tile t in registers, so the stage of tile t is free for tile t+3's
+    // data, and tile t+1 has landed once only the 12 newest loads (tile t+2) are pending.  The last step's
+    // MFMAs then cover the first fragment reads of tile t+1.
+    // A wavefront whose 64 token rows all lie past the slot's end takes part in loads and barriers only.
+    auto k_loop = [&](auto idle_tag) {
+        constexpr bool IDLE = decltype(idle_tag)::value;
+        int st = 0;
+        for (int t = 0; t < k_tiles; ++t) {
+            const int st1 = st + 1 == STAGES ? 0 : st + 1;
+            if (!IDLE) {
+                load_frags(1, st, 1);
+                mfma_step(0);
+                interleave(std::false_type{});
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(0, st, 2);
+                mfma_step(1);
+                interleave(std::false_type{});
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(1, st, 3);
+                mfma_step(0);
+                interleave(std::false_type{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            barrier_keep_loads<LX + LW>();
+            __builtin_amdgcn_sched_barrier(0);
+            if (!IDLE) load_frags(0, st1, 0);
+            issue_tile(st, t + 3);
+            if (!IDLE) {
+                mfma_step(1);
+                interleave(std::true_type{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            st = st1;
+        }
+    };
+    if (row0 + wm * 64 >= row_end) k_loop(std::true_type{});
+    else k_loop(std::false_type{});
+    // the surplus loads must have landed (as zeros) before the stages become the output image
+    barrier_keep_loads<0>();
+
+    // ---- epilogue ------------------------------------------------------------------------------------------
+    // The MFMA layout gives a lane 4 consecutive columns of 32 different token rows; stored from
+    // registers that is 8-byte scraps into 32 rows per instruction.  Instead the wavefronts put their
+    // activated, rounded results into LDS as a [128 token rows][BNO columns] bf16 image (16-byte
+    // chunk j of row r at chunk position j ^ (r & 15)), and every wavefront then stores 32 rows, 16
+    // bytes per lane, 256 or 512 contiguous bytes per row.
+    constexpr int ROWB = BNO * 2;   // bytes per image row
+    constexpr int CPR = ROWB / 16;  // chunks per image row (16 or 32)
+    if (row0 + wm * 64 < row_end) {
+#pragma unroll
+        for (int mi = 0; mi < TB; ++mi) {
+            const int r = wm * 64 + mi * 32 + (lane & 31);
+#pragma unroll
+            for (int ni = 0; ni < NB; ++ni) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    floatx4 v;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float t = acc[ni][mi][4 * g + q];
+                        if (EPI == kSwiglu) t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * acc[ni + NB][mi][4 * g + q];
+                        if (EPI == kRelu) t = fmaxf(t, 0.0f);
+                        v[q] = t;
+                    }
+                    // columns wn*(BNO/2) + ni*32 + 8g + 4*(lane/32) .. +3: chunk j, its lower or upper half
+                    const int j = wn * (BNO / 16) + ni * 4 + g;
+                    *reinterpret_cast<bf16x4*>(lds + r * ROWB + ((j ^ (r & 15)) * 16) + (lane >> 5) * 8) =
+                        __builtin_convertvector(v, bf16x4);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    constexpr int RPS = 64 / CPR;  // image rows per store instruction (4 or 2)
+    const int jc = lane % CPR;
+    const int n = n0 + jc * 8;
+#pragma unroll 4
+    for (int it = 0; it < 32 / RPS; ++it) {
+        const int r = wave * 32 + it * RPS + lane / CPR;
+        const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & 15)) * 16));
+        if (row0 + r < row_end && n < N) *reinterpret_cast<uint4*>(c + (size_t)(row0 + r) * N + n) = val;
+    }
+}
+
+template <int EPI, bool KTAIL>
+hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
+                      bf16_t* c, long long A, int S, int N, int K, int n_tiles, hipStream_t st) {
+    auto kern = mid_gemm_bf16<EPI, KTAIL>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    // every slot adds at most one partial m-tile to the A / BM whole ones
+    const long long m_tiles = A / BM + (S < A ? S : A);
+    const long long tiles = m_tiles * n_tiles;
+    const unsigned blocks = (unsigned)((tiles + XCDS - 1) / XCDS * XCDS);
+    kern<<<blocks, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, S, N, K, n_tiles);
+    return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
+                      bf16_t* c, long long A, int S, int N, int K, hipStream_t st) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
+    const int n_tiles = (N + BNO - 1) / BNO;
+    if (K % BK == 0) return launch_cfg<EPI, false>(a, gather, offsets, b0, b1, c, A, S, N, K, n_tiles, st);
+    return launch_cfg<EPI, true>(a, gather, offsets, b0, b1, c, A, S, N, K, n_tiles, st);
+}
+
+}  // namespace
+
+hipError_t launch_ffn_bf16_mid(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets,
+                               const void* w1, const void* w3, const void* w2, void* y_perm, void* ws, int passes,
+                               hipStream_t st) {
+    bf16_t* h = reinterpret_cast<bf16_t*>(static_cast<uint8_t*>(ws) + ffn_ws_layout(d).h);
+    const bf16_t* xp = static_cast<const bf16_t*>(x_perm);
+    const long long A = (long long)d.T * d.k;
+    hipError_t e = hipSuccess;
+    if (!(passes & 1)) {
+    } else if (d.act == EMOE_ACT_SWIGLU)
+        e = launch_one<kSwiglu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), static_cast<const bf16_t*>(w3), h, A,
+                                d.S, d.d_ff, d.d_model, st);
+    else
+        e = launch_one<kRelu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), nullptr, h, A, d.S, d.d_ff, d.d_model,
+                              st);
+    if (e != hipSuccess || !(passes & 2)) return e;
+    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const bf16_t*>(w2), nullptr,
+                              static_cast<bf16_t*>(y_perm), A, d.S, d.d_model, d.d_ff, st);
+}
+
+}  // namespace emoe

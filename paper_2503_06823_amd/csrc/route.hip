@@ -1,6 +1,9 @@
 // Gate logits and resident-restricted top-k (eMoE Section 1: the gate; Section 3.2.2, last
-// paragraph: a token whose expert is not on the GPU goes to its next-best expert that is),
-// fp32 inputs.  bf16 inputs take the matrix-core kernel of route_mfma.hip.
+// paragraph: a token whose expert is not on the GPU goes to its next-best expert that is):
+// fp32 inputs, and bf16 inputs when there are few tokens, few experts and long rows (a decode step
+// of a Mixtral-shaped layer).  Other bf16 batches take the matrix-core kernel of route_mfma.hip,
+// which puts 32 tokens on a workgroup: with 64 tokens it runs on two CUs, bound by the latency of
+// their walk along d_model.
 //
 // One wavefront (or, when there are few tokens, four) owns one token at a time.  Its 64 lanes
 // split the d_model axis (16 bytes per lane per step, so a step reads 1 KiB of the token row
@@ -15,6 +18,18 @@ namespace emoe {
 namespace {
 
 template <typename T> struct Vec;
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static void load(const bf16_t* p, float (&v)[8]) {
+        const uint4 r = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
 template <> struct Vec<float> {
     static constexpr int N = 4;
     __device__ static void load(const float* p, float (&v)[4]) {
@@ -61,34 +76,31 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
                 float xa[VN], xb[VN];
                 Vec<T>::load(xr + c, xa);
                 Vec<T>::load(xr + c + step, xb);
-                const T* wp = w_gate + c;  // walks down the experts' rows
+                // Rows past the last expert repeat that expert's row (their sums are never looked at):
+                // without a branch around them the loads of all rows are independent and go out together
+                // instead of one memory round trip per expert.
 #pragma unroll
                 for (int e = 0; e < EP; ++e) {
-                    if (e < E) {
-                        float wa[VN], wb[VN];
-                        Vec<T>::load(wp, wa);
-                        Vec<T>::load(wp + step, wb);
+                    const T* wp = w_gate + (size_t)(e < E ? e : E - 1) * d + c;
+                    float wa[VN], wb[VN];
+                    Vec<T>::load(wp, wa);
+                    Vec<T>::load(wp + step, wb);
 #pragma unroll
-                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xa[i], wa[i], acc[e]);
+                    for (int i = 0; i < VN; ++i) acc[e] = fmaf(xa[i], wa[i], acc[e]);
 #pragma unroll
-                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xb[i], wb[i], acc[e]);
-                        wp += d;
-                    }
+                    for (int i = 0; i < VN; ++i) acc[e] = fmaf(xb[i], wb[i], acc[e]);
                 }
             }
             if (c < d) {
                 float xa[VN];
                 Vec<T>::load(xr + c, xa);
-                const T* wp = w_gate + c;
 #pragma unroll
                 for (int e = 0; e < EP; ++e) {
-                    if (e < E) {
-                        float wa[VN];
-                        Vec<T>::load(wp, wa);
+                    const T* wp = w_gate + (size_t)(e < E ? e : E - 1) * d + c;
+                    float wa[VN];
+                    Vec<T>::load(wp, wa);
 #pragma unroll
-                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xa[i], wa[i], acc[e]);
-                        wp += d;
-                    }
+                    for (int i = 0; i < VN; ++i) acc[e] = fmaf(xa[i], wa[i], acc[e]);
                 }
             }
         }
@@ -178,6 +190,8 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
     }
 }
 
+constexpr int kWaveRouteTokens = 256;
+
 template <typename T, int EP>
 hipError_t launch_ep(const emoe_layer_desc& d, const void* x, const void* w_gate, const float* bias,
                      const int32_t* slot_of_expert, int32_t* topk_expert, float* topk_weight,
@@ -216,6 +230,11 @@ hipError_t launch_route(const emoe_layer_desc& d, const void* x, const void* w_g
                         unsigned long long* expert_tokens, hipStream_t st) {
     if (d.dtype == EMOE_F32)
         return launch_t<float>(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
+    // bf16: the matrix-core kernel runs T / 32 workgroups, each bound by the latency of its walk along
+    // d_model (11 us at d_model = 4096 however few the tokens); one workgroup per token takes 6-8 us
+    // with up to 16 experts (19 us with 64, where the matrix-core kernel stays the better one)
+    if (d.T <= kWaveRouteTokens && d.E <= 16 && d.d_model >= 2048)
+        return launch_t<bf16_t>(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
     return launch_route_bf16(d, x, w_gate, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, st);
 }
 

@@ -26,6 +26,7 @@ CASES = [
     all_resident_cfg("observe_mixtral_like", 80),
     all_resident_cfg("observe_64_experts", 81, T=777, d_model=200, E=64, k=6, zipf_s=1.2),
     all_resident_cfg("observe_32_experts_top1", 82, T=300, E=32, k=1, zipf_s=1.1),
+    all_resident_cfg("observe_few_tokens_long_rows", 85, T=70, d_model=2048, E=16, k=2, zipf_s=1.1),
     all_resident_cfg("observe_f32", 83, T=150, d_model=72, E=16, k=2, dtype="f32"),
     all_resident_cfg("observe_f32_many_tokens", 84, T=2500, d_model=64, E=8, k=2, dtype="f32"),
 ]

@@ -45,20 +45,14 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int BM = 128;                    // token rows per tile
-constexpr int BR = 256;                    // weight rows per tile (SwiGLU: 128 of W1 + 128 of W3)
 constexpr int BK = 64;                     // K elements per tile
 constexpr int ROW_BYTES = BK * 2;          // 128
 constexpr int X_TILE = BM * ROW_BYTES;     // 16 KiB
-constexpr int W_TILE = BR * ROW_BYTES;     // 32 KiB
-constexpr int STAGE_BYTES = X_TILE + W_TILE;
-constexpr int STAGES = 3;
-constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;  // 144 KiB
 constexpr int NW = 4;                      // wavefronts: 2 (tokens) x 2 (weight rows)
 constexpr int TB = 2;                      // 32-token blocks per wavefront
-constexpr int WB = 4;                      // 32-row weight blocks per wavefront
 constexpr int LX = BM / 8 / NW;            // token load instructions per wavefront and K tile (4)
-constexpr int LW = BR / 8 / NW;            // weight load instructions per wavefront and K tile (8)
 constexpr int XCDS = 8;
+constexpr int kCUs = 256;
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
 
@@ -75,13 +69,22 @@ __device__ __forceinline__ void barrier_keep_loads() {
     asm volatile("" ::: "memory");
 }
 
-template <int EPI, bool KTAIL>
+// BR: weight rows per tile, 256 or 128 (SwiGLU: half of them rows of W1, half the same rows of W3).
+// STAGES: LDS stages of one K tile each (token rows + weight rows), STAGES - 1 of them in flight.
+template <int EPI, int BR, int STAGES, bool KTAIL>
 __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
                                                      const int32_t* __restrict__ offsets,
                                                      const bf16_t* __restrict__ b0, const bf16_t* __restrict__ b1,
                                                      bf16_t* __restrict__ c, int S, int N, int K, int n_tiles) {
+    constexpr int W_TILE = BR * ROW_BYTES;             // 32 or 16 KiB
+    constexpr int STAGE_BYTES = X_TILE + W_TILE;
+    constexpr int WB = BR / 2 / 32;                    // 32-row weight blocks per wavefront (4 or 2)
+    constexpr int LW = BR / 8 / NW;                    // weight load instructions per wavefront and K tile
+    constexpr int LPT = LX + LW;                       // loads per wavefront and K tile
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;   // output column blocks per wavefront
+    static_assert((STAGES - 1) * LPT <= 63, "vmcnt counts 63 loads");
+    static_assert(BM * BNO * 2 <= STAGES * STAGE_BYTES, "the output image reuses the stages");
     extern __shared__ __align__(16) char lds[];
 
     const int tid = threadIdx.x;
@@ -182,8 +185,8 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
         int rr;
-        if (EPI == kSwiglu) rr = (i < WB / 2) ? wn * 64 + i * 32 : BR / 2 + wn * 64 + (i - WB / 2) * 32;
-        else rr = wn * 128 + i * 32;
+        if (EPI == kSwiglu) rr = (i < WB / 2) ? wn * (BR / 4) + i * 32 : BR / 2 + wn * (BR / 4) + (i - WB / 2) * 32;
+        else rr = wn * (BR / 2) + i * 32;
         w_off[i] = X_TILE + (rr + f_row) * ROW_BYTES + f_sw;
     }
 
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
             for (int mi = 0; mi < TB; ++mi)
                 acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
     };
-    // a step's eight MFMAs with its six fragment reads and (in the step after the barrier) the twelve
+    // a step's MFMAs with its fragment reads and (in the step after the barrier) the tile's
     // global->LDS loads slotted between them, so that no memory instruction queues up behind another
     auto interleave = [&](auto with_loads) {
         constexpr bool LOADS = decltype(with_loads)::value;
@@ -219,23 +222,22 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
         for (int i = 0; i < TB * WB; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
             if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one LDS read
-            if (LOADS) __builtin_amdgcn_sched_group_barrier(0x010, (LX + LW + TB * WB - 1) / (TB * WB), 0);  // VMEM
+            if (LOADS) __builtin_amdgcn_sched_group_barrier(0x010, (LPT + TB * WB - 1) / (TB * WB), 0);  // VMEM
         }
     };
 
-    // ---- prologue: tiles 0, 1 and 2 on their way, tile 0 landed, its first fragments read -----------
-    issue_tile(0, 0);
-    issue_tile(1, 1);
-    issue_tile(2, 2);
-    barrier_keep_loads<2 * (LX + LW)>();
+    // ---- prologue: tiles 0 .. STAGES-1 on their way, tile 0 landed, its first fragments read --------
+#pragma unroll
+    for (int p = 0; p < STAGES; ++p) issue_tile(p, p);
+    barrier_keep_loads<(STAGES - 1) * LPT>();
     load_frags(0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- main loop -------------------------------------------------------------------------------------
     // Per K tile four MFMA steps of 16.  The barrier comes before the last step: by then every wavefront
-    // holds its last fragments of tile t in registers, so the stage of tile t is free for tile t+3's
-    // data, and tile t+1 has landed once only the 12 newest loads (tile t+2) are pending.  The last step's
-    // MFMAs then cover the first fragment reads of tile t+1.
+    // holds its last fragments of tile t in registers, so the stage of tile t is free for the data of
+    // tile t+STAGES, and tile t+1 has landed once only the loads of tiles t+2 .. t+STAGES-1 are pending.
+    // The last step's MFMAs then cover the first fragment reads of tile t+1.
     // A wavefront whose 64 token rows all lie past the slot's end takes part in loads and barriers only.
     auto k_loop = [&](auto idle_tag) {
         constexpr bool IDLE = decltype(idle_tag)::value;
@@ -256,10 +258,10 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                 interleave(std::false_type{});
             }
             __builtin_amdgcn_sched_barrier(0);
-            barrier_keep_loads<LX + LW>();
+            barrier_keep_loads<(STAGES - 2) * LPT>();
             __builtin_amdgcn_sched_barrier(0);
             if (!IDLE) load_frags(0, st1, 0);
-            issue_tile(st, t + 3);
+            issue_tile(st, t + STAGES);
             if (!IDLE) {
                 mfma_step(1);
                 interleave(std::true_type{});
@@ -277,10 +279,11 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
     // The MFMA layout gives a lane 4 consecutive columns of 32 different token rows; stored from
     // registers that is 8-byte scraps into 32 rows per instruction.  Instead the wavefronts put their
     // activated, rounded results into LDS as a [128 token rows][BNO columns] bf16 image (16-byte
-    // chunk j of row r at chunk position j ^ (r & 15)), and every wavefront then stores 32 rows, 16
-    // bytes per lane, 256 or 512 contiguous bytes per row.
+    // chunk j of row r at chunk position j ^ (r & SWM)), and every wavefront then stores 32 rows, 16
+    // bytes per lane, whole row segments of 2 BNO bytes.
     constexpr int ROWB = BNO * 2;   // bytes per image row
-    constexpr int CPR = ROWB / 16;  // chunks per image row (16 or 32)
+    constexpr int CPR = ROWB / 16;  // chunks per image row (8, 16 or 32)
+    constexpr int SWM = CPR - 1 < 15 ? CPR - 1 : 15;
     if (row0 + wm * 64 < row_end) {
 #pragma unroll
         for (int mi = 0; mi < TB; ++mi) {
@@ -299,50 +302,64 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                     }
                     // columns wn*(BNO/2) + ni*32 + 8g + 4*(lane/32) .. +3: chunk j, its lower or upper half
                     const int j = wn * (BNO / 16) + ni * 4 + g;
-                    *reinterpret_cast<bf16x4*>(lds + r * ROWB + ((j ^ (r & 15)) * 16) + (lane >> 5) * 8) =
+                    *reinterpret_cast<bf16x4*>(lds + r * ROWB + ((j ^ (r & SWM)) * 16) + (lane >> 5) * 8) =
                         __builtin_convertvector(v, bf16x4);
                 }
             }
         }
     }
     __syncthreads();
-    constexpr int RPS = 64 / CPR;  // image rows per store instruction (4 or 2)
+    constexpr int RPS = 64 / CPR;  // image rows per store instruction
     const int jc = lane % CPR;
     const int n = n0 + jc * 8;
 #pragma unroll 4
     for (int it = 0; it < 32 / RPS; ++it) {
         const int r = wave * 32 + it * RPS + lane / CPR;
-        const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & 15)) * 16));
+        const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & SWM)) * 16));
         if (row0 + r < row_end && n < N) *reinterpret_cast<uint4*>(c + (size_t)(row0 + r) * N + n) = val;
     }
 }
 
-template <int EPI, bool KTAIL>
+template <int EPI, int BR, int STAGES, bool KTAIL>
 hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
-                      bf16_t* c, long long A, int S, int N, int K, int n_tiles, hipStream_t st) {
-    auto kern = mid_gemm_bf16<EPI, KTAIL>;
+                      bf16_t* c, long long m_tiles, int S, int N, int K, hipStream_t st) {
+    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
+    constexpr int kLds = STAGES * (X_TILE + BR * ROW_BYTES);
+    static_assert(kLds <= 160 * 1024, "LDS of one CU");
+    auto kern = mid_gemm_bf16<EPI, BR, STAGES, KTAIL>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    // every slot adds at most one partial m-tile to the A / BM whole ones
-    const long long m_tiles = A / BM + (S < A ? S : A);
+    const int n_tiles = (N + BNO - 1) / BNO;
     const long long tiles = m_tiles * n_tiles;
     const unsigned blocks = (unsigned)((tiles + XCDS - 1) / XCDS * XCDS);
-    kern<<<blocks, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, S, N, K, n_tiles);
+    kern<<<blocks, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, S, N, K, n_tiles);
     return hipGetLastError();
+}
+
+template <int EPI, int BR, int STAGES>
+hipError_t launch_ktail(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
+                        bf16_t* c, long long m_tiles, int S, int N, int K, hipStream_t st) {
+    if (K % BK == 0) return launch_cfg<EPI, BR, STAGES, false>(a, gather, offsets, b0, b1, c, m_tiles, S, N, K, st);
+    return launch_cfg<EPI, BR, STAGES, true>(a, gather, offsets, b0, b1, c, m_tiles, S, N, K, st);
 }
 
 template <int EPI>
 hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
                       bf16_t* c, long long A, int S, int N, int K, hipStream_t st) {
-    constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
-    const int n_tiles = (N + BNO - 1) / BNO;
-    if (K % BK == 0) return launch_cfg<EPI, false>(a, gather, offsets, b0, b1, c, A, S, N, K, n_tiles, st);
-    return launch_cfg<EPI, true>(a, gather, offsets, b0, b1, c, A, S, N, K, n_tiles, st);
+    // every slot adds at most one partial m-tile to the A / BM whole ones
+    const long long m_tiles = A / BM + (S < A ? S : A);
+    // Tiles of 256 weight rows, unless they would leave CUs without a tile (the second product of a
+    // layer with a small d_model): then 128 weight rows and five stages, so that twice as many CUs
+    // stream weights, each with as many bytes in flight.
+    constexpr int BNO = EPI == kSwiglu ? 128 : 256;
+    if (m_tiles * ((N + BNO - 1) / BNO) <= kCUs)
+        return launch_ktail<EPI, 128, 5>(a, gather, offsets, b0, b1, c, m_tiles, S, N, K, st);
+    return launch_ktail<EPI, 256, 3>(a, gather, offsets, b0, b1, c, m_tiles, S, N, K, st);
 }
 
 }  // namespace

@@ -31,6 +31,9 @@ SMALL_CASES = [
     cfg("mid_relu_skewed", act="relu", T=1500, d_model=256, d_ff=520, E=64, k=1, R=16, zipf_s=1.1, index=45),
     cfg("mid_long_k_ktail", T=280, d_model=1032, d_ff=1160, E=8, k=2, R=4, S=6, index=58),
     cfg("mid_topk6", T=380, d_model=256, d_ff=384, E=64, k=6, R=24, zipf_s=1.2, resident="popular", index=46),
+    # enough output tiles that the first product takes tiles of 256 weight rows (all other small cases take 128)
+    cfg("mid_relu_wide_ff", act="relu", T=1500, d_model=72, d_ff=2560, E=64, k=1, R=16, zipf_s=1.1, index=66),
+    cfg("mid_swiglu_wide_ff", T=800, d_model=72, d_ff=1408, E=16, k=2, R=16, index=67),
     cfg("mid_few_rows_per_slot", T=100, d_model=192, d_ff=264, E=8, k=2, R=5, index=60),
     # tiles of 256 token rows (A > 100 S): several M tiles + tail, N tails, K tail
     cfg("tiled_swiglu_ragged", T=1700, d_model=328, d_ff=456, E=8, k=2, R=4, index=61),

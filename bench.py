@@ -253,7 +253,7 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the upload measurement and the C5 / C2 workloads")
     ap.add_argument("--more-shapes", action="store_true",
-                    help="also time a Mixtral-8x22B-shaped prefill layer and an OpenMoE-shaped layer")
+                    help="also time a Mixtral-8x22B-shaped prefill layer, an OpenMoE-shaped layer and one short prompt at the Mixtral-8x7B shape")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = size the sample for about 15 s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy, so that a hardware-counter run of this "
@@ -357,6 +357,10 @@ def main():
         result["x2"] = other_config(torch, P, gen, gen.X2, 20, 5, 1,
                                     "X2 OpenMoE-shaped layer: T=2048 d_model=2048 d_ff=8192 E=32 top-2 SwiGLU, 16 of 32 "
                                     "resident, Zipf(1.1) gate bias, bf16")
+
+        result["x3"] = other_config(torch, P, gen, gen.X3, 30, 5, 3,
+                                    "X3 one short prompt at the Mixtral-8x7B shape: T=256 d_model=4096 d_ff=14336 E=8 "
+                                    "top-2 SwiGLU, 6 of 8 resident, bf16; 3 rotating copies of the slot buffers")
 
     # ---------------- the oracle on the host cores, on a bounded sample of the prefill workload ------------
     if not args.no_cpu_baseline:

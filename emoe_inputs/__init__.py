@@ -86,10 +86,12 @@ C5 = LayerConfig("C5_finegrained_bf16", 4, 8192, 2048, 1408, 64, 6, 24, BF16, SW
                  zipf_s=1.2, resident="popular")
 CONFIGS = {"C1": C1, "C2": C2, "C3": C3, "C4": C4, "C5": C5}
 # Further shapes of the model families the paper serves (Section 2.1), not part of the graded five:
-# a Mixtral-8x22B-shaped prefill layer and an OpenMoE-shaped layer (32 experts, top-2, half resident).
+# a Mixtral-8x22B-shaped prefill layer, an OpenMoE-shaped layer (32 experts, top-2, half resident)
 X1 = LayerConfig("X1_mixtral_8x22b_prefill_bf16", 5, 4096, 6144, 16384, 8, 2, 4, BF16, SWIGLU)
 X2 = LayerConfig("X2_openmoe_like_bf16", 6, 2048, 2048, 8192, 32, 2, 16, BF16, SWIGLU, zipf_s=1.1)
-EXTRA_CONFIGS = {"X1": X1, "X2": X2}
+# one short prompt at the Mixtral-8x7B shape (a few dozen rows per expert: between a decode step and a batch of prompts)
+X3 = LayerConfig("X3_mixtral_one_prompt_bf16", 7, 256, 4096, 14336, 8, 2, 6, BF16, SWIGLU)
+EXTRA_CONFIGS = {"X1": X1, "X2": X2, "X3": X3}
 
 
 def small_variant(cfg: LayerConfig, *, T: Optional[int] = None, d_model: Optional[int] = None,

@@ -31,6 +31,7 @@
 // go round-robin over the 8 XCDs, so ids are remapped so that an XCD works on consecutive tiles:
 // the m-tiles that share a weight panel run at the same time behind the same L2, and the panel is
 // fetched from HBM once.
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -327,12 +328,12 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
     constexpr int kLds = STAGES * (X_TILE + BR * ROW_BYTES);
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     auto kern = mid_gemm_bf16<EPI, BR, STAGES, KTAIL>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};  // set once per kernel; setting it twice from two threads is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int n_tiles = (N + BNO - 1) / BNO;
     const long long tiles = m_tiles * n_tiles;

@@ -40,6 +40,7 @@
 // ids are remapped: the workgroups of an XCD hold consecutive tiles of an order in which 32
 // consecutive tiles form a block of 8 m-tiles x 4 n-tiles of one slot (see tile_in_slot), so that
 // XCD's L2 supplies 12 operand panels for 32 tiles.
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -569,12 +570,12 @@ template <int EPI, bool KTAIL>
 hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1, bf16_t* c,
                       float* partials, int S, int N, int K, int n_tiles, hipStream_t st) {
     auto kern = grouped_gemm_bf16<EPI, KTAIL>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};  // set once per kernel; setting it twice from two threads is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
     splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, reinterpret_cast<const int*>(partials),

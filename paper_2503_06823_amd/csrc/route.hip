@@ -9,8 +9,9 @@
 // split the d_model axis (16 bytes per lane per step, so a step reads 1 KiB of the token row
 // contiguously); every lane keeps one
 // partial sum per expert.  A butterfly reduce-scatter then leaves expert e's complete logit in
-// lane e*(64/EP): 63 shuffles for 64 experts instead of 64 full reductions.  Top-k is k rounds
-// of a wave-wide arg-max on (logit, lower index wins); softmax over the k winners.
+// lanes e*(64/EP) .. +64/EP-1: 63 shuffles for 64 experts instead of 64 full reductions.  The logits
+// are then read into scalar registers and top-k is k rounds of compares that every lane performs
+// on the same values (lower index wins a tie); softmax over the k winners.
 // The summation order is fixed by the code, so results are reproducible run to run.
 #include "common.h"
 
@@ -133,57 +134,57 @@ __global__ __launch_bounds__(256) void route_kernel(const T* __restrict__ x, con
         if (!live) continue;
         logit += my_bias;
 
-        // k rounds of arg-max over resident experts not taken yet
-        bool avail = resident;
-        float sel_v = 0.0f, top_v = 0.0f;
+        // Every lane of a group holds its expert's logit.  One lane per expert is read into scalar
+        // registers, so that the k rounds of "largest logit among the resident experts not taken yet,
+        // lower index on a tie" are plain compares on values every lane already has - no exchange
+        // between lanes, whose latency would otherwise be paid 18 times per round.
+        float lg[EP];
+#pragma unroll
+        for (int e = 0; e < EP; ++e)
+            lg[e] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(logit), e * (64 / EP)));
+        const unsigned long long res_lanes = __ballot(resident);
+        unsigned long long avail = 0;  // bit e: expert e is resident and not taken yet
+#pragma unroll
+        for (int e = 0; e < EP; ++e) avail |= ((res_lanes >> (e * (64 / EP))) & 1ull) << e;
+        float sel_v = 0.0f, top_v = 0.0f, sum = 0.0f;
         int sel_e = 0;
         for (int j = 0; j < k; ++j) {
-            float bv = logit;
-            int be = my_e;
-            bool bo = avail;
+            float bv = 0.0f;
+            int be = -1;
 #pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) {
-                float ov = __shfl_xor(bv, m);
-                int oe = __shfl_xor(be, m);
-                bool oo = __shfl_xor((int)bo, m) != 0;
-                bool take = oo && (!bo || ov > bv || (ov == bv && oe < be));
-                if (take) { bv = ov; be = oe; bo = true; }
+            for (int e = 0; e < EP; ++e) {
+                const bool ok = (avail >> e) & 1ull;
+                if (ok && (be < 0 || lg[e] > bv)) { bv = lg[e]; be = e; }
             }
-            if (!bo) {  // fewer than k resident experts: precondition broken, stay defined
+            if (be < 0) {  // fewer than k resident experts: precondition broken, stay defined
                 be = 0;
                 bv = 0.0f;
+            } else {
+                avail &= ~(1ull << be);
             }
-            if (my_e == be) avail = false;
             if (j == 0) top_v = bv;
+            sum += expf(bv - top_v);
             if (lane == j) { sel_v = bv; sel_e = be; }
         }
-        float p = lane < k ? expf(sel_v - top_v) : 0.0f;
-        float sum = p;
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m);
         if (lane < k) {
             topk_expert[(size_t)t * k + lane] = sel_e;
-            topk_weight[(size_t)t * k + lane] = p / sum;
+            topk_weight[(size_t)t * k + lane] = expf(sel_v - top_v) / sum;
         }
         // Workload (Section 3.2.2: the number of tokens an expert receives): the same k rounds over
         // all E experts, resident or not.  Integer counts: the accumulated result has no order.
         if (expert_tokens != nullptr) {
-            bool left = my_e < E;
+            unsigned long long left = E >= 64 ? ~0ull : (1ull << E) - 1ull;
             int obs_e = -1;
             for (int j = 0; j < k; ++j) {
-                float bv = logit;
-                int be = my_e;
-                bool bo = left;
+                float bv = 0.0f;
+                int be = -1;
 #pragma unroll
-                for (int m = 32; m >= 1; m >>= 1) {
-                    float ov = __shfl_xor(bv, m);
-                    int oe = __shfl_xor(be, m);
-                    bool oo = __shfl_xor((int)bo, m) != 0;
-                    bool take = oo && (!bo || ov > bv || (ov == bv && oe < be));
-                    if (take) { bv = ov; be = oe; bo = true; }
+                for (int e = 0; e < EP; ++e) {
+                    const bool ok = (left >> e) & 1ull;
+                    if (ok && (be < 0 || lg[e] > bv)) { bv = lg[e]; be = e; }
                 }
-                if (bo && my_e == be) left = false;
-                if (lane == j) obs_e = bo ? be : -1;
+                if (be >= 0) left &= ~(1ull << be);
+                if (lane == j) obs_e = be;
             }
             if (lane < k && obs_e >= 0) atomicAdd(&expert_tokens[obs_e], 1ull);
         }

@@ -21,6 +21,8 @@
 // being in lane^32.  Top-k is k rounds of: best available logit of this lane (ascending expert
 // order, strict comparison, so the lower index wins a tie), one exchange with the partner lane,
 // winner marked taken.  Weights are the softmax over the k winners.
+#include <atomic>
+
 #include "common.h"
 
 namespace emoe {
@@ -277,12 +279,12 @@ hipError_t launch_cfg(const emoe_layer_desc& d, const bf16_t* x, const bf16_t* w
     constexpr int kLds = STAGES * (WR * ROW_BYTES + X_BYTES) + kMaxExperts * 12;
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     auto kern = route_mfma_kernel<WR, STAGES, KTAIL>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};  // set once per kernel; setting it twice from two threads is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     kern<<<(d.T + TOK - 1) / TOK, 256, kLds, st>>>(x, wg, bias, slot_of_expert, topk_expert, topk_weight, expert_tokens, d.T,
                                                   d.d_model, d.E, d.k);

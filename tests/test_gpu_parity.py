@@ -140,3 +140,39 @@ def test_all_experts_resident_equals_the_ordinary_layer(gpu_device):
     torch.cuda.synchronize()
     check_routing_and_permutation(dl, ref)
     check_outputs(dl, ref)
+
+
+def _random_cases(n, seed):
+    """Seeded random small layers over every path: dtype, activation, extents with and without tails,
+    few to many rows per slot, more slots than residents."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        dtype = "f32" if i % 6 == 5 else "bf16"
+        act = "relu" if rng.random() < 0.3 else "swiglu"
+        E = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+        R = int(rng.integers(1, E + 1))
+        k = int(rng.integers(1, min(R, 6) + 1))
+        S = int(rng.integers(R, E + 1))
+        rows = int(rng.choice([3, 12, 30, 45, 70, 95, 110, 200, 420]))      # per slot, on average
+        T = max(1, min(2500, rows * S // k))
+        d_model = int(rng.choice([64, 72, 128, 200, 256, 328]))
+        d_ff = int(rng.choice([64, 136, 192, 264, 520]))
+        if dtype == "f32":
+            T, d_model, d_ff = min(T, 300), min(d_model, 128), min(d_ff, 192)
+        zipf = float(rng.choice([0.0, 0.0, 1.1]))
+        cases.append(cfg(f"random{i}_{dtype}_{act}_T{T}_d{d_model}_f{d_ff}_E{E}_k{k}_R{R}_S{S}", dtype=dtype, act=act, T=T,
+                         d_model=d_model, d_ff=d_ff, E=E, k=k, R=R, S=S, zipf_s=zipf, index=100 + i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_cases(30, 20250306), ids=lambda c: c.name)
+def test_random_small_layers(gpu_device, c):
+    inp = gen.make_layer_inputs(c, shuffle_slots=c.index % 2 == 1 and c.slots > 1)
+    ref = oracle.layer_forward(inp)
+    dl = DeviceLayer(inp)
+    dl.forward()
+    torch.cuda.synchronize()
+    check_routing_and_permutation(dl, ref)
+    check_outputs(dl, ref)
+    dl.check_gather_path_is_identical()

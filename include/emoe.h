@@ -165,6 +165,21 @@ int emoe_combine(const emoe_layer_desc *desc, const void *y_perm, const int32_t 
                  const float *topk_weight, void *out, void *stream);
 
 /*
+ * The whole layer (Section 1: a gate and a collection of experts, here over the resident
+ * experts only, Section 3.2.2): emoe_route, emoe_permute (indices only), emoe_expert_ffn_gather
+ * and emoe_combine enqueued in this order on `stream`, with the same arguments, results and
+ * errors as the four calls; nothing else is done and nothing is allocated.  All the intermediate
+ * results are caller buffers as in the single calls (x_perm is not needed: the FFN reads the
+ * token rows through perm).  Validation of all arguments happens before the first launch, so an
+ * error leaves every output untouched.
+ */
+int emoe_layer_forward(const emoe_layer_desc *desc, const void *x, const void *w_gate, const float *gate_bias,
+                       const int32_t *slot_of_expert, const void *w1_slots, const void *w3_slots,
+                       const void *w2_slots, int32_t *topk_expert, float *topk_weight, int32_t *slot_counts,
+                       int32_t *slot_offsets, int32_t *perm, int32_t *inv_perm, void *y_perm, void *out,
+                       void *permute_ws, size_t permute_ws_bytes, void *ffn_ws, size_t ffn_ws_bytes, void *stream);
+
+/*
  * Change the resident set (Section 3.2.2: predicted experts not yet on the GPU are
  * loaded, the others leave; Section 4: loads are asynchronous host-to-device copies,
  * the layer waits on an event recorded after its load so it never sees stale

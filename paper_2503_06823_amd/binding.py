@@ -23,7 +23,8 @@ DTYPES = {"f32": EMOE_F32, "bf16": EMOE_BF16}
 ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
 
 EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_route_observe", "emoe_permute",
-           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_combine", "emoe_load_experts", "emoe_expected_tokens",
+           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_combine",
+           "emoe_layer_forward", "emoe_load_experts", "emoe_expected_tokens",
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
            "emoe_loader_residents", "emoe_loader_synchronize", "emoe_expected_latency", "emoe_schedule",
@@ -63,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.emoe_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_expert_ffn_pass.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.emoe_layer_forward.argtypes = [dp] + [vp] * 15 + [vp, sz, vp, sz, vp]
         L.emoe_load_experts.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
@@ -178,6 +180,17 @@ def emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream=None, check=Tr
     rc = lib().emoe_combine(ctypes.byref(desc), _ptr(y_perm), _ptr(inv_perm), _ptr(topk_weight), _ptr(out),
                             _stream(stream))
     return _check(rc, "emoe_combine", check)
+
+
+def emoe_layer_forward(desc, x, w_gate, gate_bias, slot_of_expert, w1_slots, w3_slots, w2_slots, topk_expert, topk_weight,
+                       slot_counts, slot_offsets, perm, inv_perm, y_perm, out, permute_ws, permute_ws_bytes, ffn_ws,
+                       ffn_ws_bytes, stream=None, check=True) -> int:
+    rc = lib().emoe_layer_forward(ctypes.byref(desc), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(slot_of_expert),
+                                  _ptr(w1_slots), _ptr(w3_slots), _ptr(w2_slots), _ptr(topk_expert), _ptr(topk_weight),
+                                  _ptr(slot_counts), _ptr(slot_offsets), _ptr(perm), _ptr(inv_perm), _ptr(y_perm),
+                                  _ptr(out), _ptr(permute_ws), int(permute_ws_bytes), _ptr(ffn_ws), int(ffn_ws_bytes),
+                                  _stream(stream))
+    return _check(rc, "emoe_layer_forward", check)
 
 
 def _i32_array(values: Optional[Sequence[int]]):

@@ -202,6 +202,32 @@ int emoe_combine(const emoe_layer_desc* desc, const void* y_perm, const int32_t*
     return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
 }
 
+int emoe_layer_forward(const emoe_layer_desc* desc, const void* x, const void* w_gate, const float* gate_bias,
+                       const int32_t* slot_of_expert, const void* w1_slots, const void* w3_slots,
+                       const void* w2_slots, int32_t* topk_expert, float* topk_weight, int32_t* slot_counts,
+                       int32_t* slot_offsets, int32_t* perm, int32_t* inv_perm, void* y_perm, void* out,
+                       void* permute_ws, size_t permute_ws_bytes, void* ffn_ws, size_t ffn_ws_bytes, void* stream) {
+    // everything the four calls would reject, before anything is enqueued
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!x || !w_gate || !slot_of_expert || !w1_slots || !w2_slots || !topk_expert || !topk_weight || !slot_counts ||
+        !slot_offsets || !perm || !inv_perm || !y_perm || !out)
+        return EMOE_ERR_NULL;
+    if (desc->act == EMOE_ACT_SWIGLU && !w3_slots) return EMOE_ERR_NULL;
+    if (desc->act == EMOE_ACT_RELU && w3_slots) return EMOE_ERR_UNSUPPORTED;
+    if (!permute_ws || permute_ws_bytes < permute_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
+    if (!ffn_ws || ffn_ws_bytes < ffn_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
+    rc = emoe_route(desc, x, w_gate, gate_bias, slot_of_expert, topk_expert, topk_weight, stream);
+    if (rc != EMOE_OK) return rc;
+    rc = emoe_permute(desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm, nullptr, permute_ws,
+                      permute_ws_bytes, stream);
+    if (rc != EMOE_OK) return rc;
+    rc = emoe_expert_ffn_gather(desc, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ffn_ws, ffn_ws_bytes,
+                                stream);
+    if (rc != EMOE_OK) return rc;
+    return emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream);
+}
+
 int emoe_load_experts(const emoe_layer_desc* desc, int32_t n, const int32_t* expert_ids, const int32_t* slot_ids,
                       const void* const* host_w1, const void* const* host_w3, const void* const* host_w2,
                       void* w1_slots, void* w3_slots, void* w2_slots, int32_t* slot_of_expert,

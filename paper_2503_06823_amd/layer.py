@@ -75,11 +75,17 @@ class DeviceInputs:
 
 
 def layer_forward(buf: LayerBuffers, x, w_gate, gate_bias, slot_of_expert, w1_slots, w3_slots, w2_slots,
-                  stream=None, gather_in_ffn: bool = True) -> torch.Tensor:
+                  stream=None, gather_in_ffn: bool = True, one_call: bool = False) -> torch.Tensor:
     """Enqueue the four calls on one stream; returns buf.out (no host synchronisation).
     `gather_in_ffn`: the FFN reads the token rows through perm (buf.x_perm stays unwritten); otherwise
-    emoe_permute copies them into buf.x_perm first."""
+    emoe_permute copies them into buf.x_perm first.  `one_call`: the same four steps through the
+    library's emoe_layer_forward (implies gather_in_ffn)."""
     d = buf.desc
+    if one_call:
+        B.emoe_layer_forward(d, x, w_gate, gate_bias, slot_of_expert, w1_slots, w3_slots, w2_slots, buf.topk_expert,
+                             buf.topk_weight, buf.slot_counts, buf.slot_offsets, buf.perm, buf.inv_perm, buf.y_perm,
+                             buf.out, buf.permute_ws, buf.permute_ws.numel(), buf.ffn_ws, buf.ffn_ws.numel(), stream)
+        return buf.out
     B.emoe_route(d, x, w_gate, gate_bias, slot_of_expert, buf.topk_expert, buf.topk_weight, stream)
     B.emoe_permute(d, x, buf.topk_expert, slot_of_expert, buf.slot_counts, buf.slot_offsets, buf.perm, buf.inv_perm,
                    None if gather_in_ffn else buf.x_perm, buf.permute_ws, buf.permute_ws.numel(), stream)

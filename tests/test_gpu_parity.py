@@ -176,3 +176,25 @@ def test_random_small_layers(gpu_device, c):
     check_routing_and_permutation(dl, ref)
     check_outputs(dl, ref)
     dl.check_gather_path_is_identical()
+
+
+@pytest.mark.parametrize("name", ["mid_swiglu_ragged", "tiled_relu_skewed", "stream_decode", "C1_tiny_f32"])
+def test_layer_forward_in_one_call_equals_the_four_calls(gpu_device, name):
+    c = [c for c in SMALL_CASES if c.name == name][0]
+    inp = gen.make_layer_inputs(c)
+    a, b = DeviceLayer(inp), DeviceLayer(inp)
+    P.layer_forward(a.buf, a.x, a.w_gate, a.gate_bias, a.slot_of_expert, a.w1, a.w3, a.w2, gather_in_ffn=True)
+    P.layer_forward(b.buf, b.x, b.w_gate, b.gate_bias, b.slot_of_expert, b.w1, b.w3, b.w2, one_call=True)
+    torch.cuda.synchronize()
+    for f in ("topk_expert", "topk_weight", "slot_counts", "slot_offsets", "perm", "inv_perm", "y_perm", "out"):
+        assert torch.equal(getattr(a.buf, f), getattr(b.buf, f)), f
+    # an argument error is found before anything is enqueued: outputs stay as they are
+    before = b.buf.out.clone()
+    b.buf.out.zero_()
+    rc = P.emoe_layer_forward(b.desc, b.x, b.w_gate, b.gate_bias, b.slot_of_expert, b.w1, b.w3, b.w2, b.buf.topk_expert,
+                              b.buf.topk_weight, b.buf.slot_counts, b.buf.slot_offsets, b.buf.perm, b.buf.inv_perm,
+                              b.buf.y_perm, b.buf.out, b.buf.permute_ws, b.buf.permute_ws.numel(), b.buf.ffn_ws,
+                              b.buf.ffn_ws.numel() - 1, check=False)
+    torch.cuda.synchronize()
+    assert rc == P.EMOE_ERR_WORKSPACE
+    assert not b.buf.out.any() and before.any()

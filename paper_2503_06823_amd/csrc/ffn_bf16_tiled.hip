@@ -34,6 +34,13 @@
 // Epilogue: results go through LDS so that they leave as whole 256- or 512-byte row segments (see
 // epilogue()); accumulators are read from their AGPRs one block at a time.
 //
+// Slots that do not fill their tiles: a slot's rows are spread evenly over its m-tiles in whole
+// 32-row MFMA blocks (257 rows: tiles of 160 and 97 rows, not 256 and 1), a tile's blocks alternate
+// between the two rows of wavefronts, and the K loop is compiled for 0 .. 4 blocks per wavefront, so
+// that matrix work is done for blocks with rows only and both wavefront rows finish together.  A
+// tile still costs a pass over its weight panel whatever it holds (8 slots of 257 rows at the Mixtral
+// shape: 0.96 -> 0.88 ms; of 513 rows: 1.51 -> 1.41 ms; full tiles unchanged).
+//
 // Ragged groups: group sizes live on the device.  The launch is persistent (one workgroup per CU);
 // every workgroup derives the list of (slot, m-tile, n-tile) tiles from slot_offsets and takes its
 // share (see "work distribution" below).  Workgroup ids are dealt round-robin to the 8 XCDs, so
@@ -148,7 +155,24 @@ __device__ __forceinline__ void tile_in_slot(int rem, int m_tiles, int n_tiles, 
     nt = group * kBlockN + r / mb;
 }
 
-// tile number -> slot, first row, end of the slot's rows, n-tile
+// Rows per m-tile of a slot of `rows` rows cut into `tiles` tiles: the rows are spread evenly (in
+// whole 32-row MFMA blocks), so that a slot of 257 rows becomes tiles of 160 and 97 rows instead of
+// 256 and 1.  A tile costs a pass over its weight panel whatever it holds; what is saved is the
+// matrix work of the blocks without rows, which both tiles then skip.
+__device__ __forceinline__ int rows_per_tile(int rows, int tiles) {
+    const int even = (rows + tiles - 1) / (tiles > 0 ? tiles : 1);
+    return (even + 31) & ~31;  // <= BM, so tile number `tiles - 1` still starts inside the slot
+}
+
+// Which wavefronts multiply which of a tile's 32-row token blocks: the blocks alternate between
+// the two wavefront rows, so that both finish together whatever the number of blocks that hold rows.
+// -> tile block of block i of wavefront row wm, and the number of its blocks that hold rows.
+__device__ __forceinline__ int tile_block(int wm, int i) { return 2 * i + wm; }
+__device__ __forceinline__ int blocks_of_wavefront(int row0, int row_end, int wm) {
+    return ((row_end - row0 + 31) / 32 - wm + 1) / 2;
+}
+
+// tile number -> slot, first row and end of the tile's rows, n-tile
 __device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets, int S, int n_tiles, int L, int& slot,
                                             int& row0, int& row_end, int& nt) {
     int rem = L;
@@ -161,8 +185,9 @@ __device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets,
             slot = s;
             int mt;
             tile_in_slot(rem, tiles, n_tiles, mt, nt);
-            row0 = b + mt * BM;
-            row_end = e;
+            const int rpt = rows_per_tile(e - b, tiles);
+            row0 = b + mt * rpt;
+            row_end = row0 + rpt < e ? row0 + rpt : e;
             return;
         }
         rem -= span;
@@ -177,7 +202,7 @@ __device__ __forceinline__ void epilogue_block(const floatx16& gate, const float
                                                int row0, int row_end, int n0, int N, int wm, int wn, int mi, int ni,
                                                int lane) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
-    const int r = row0 + wm * 128 + mi * 32 + (lane & 31);
+    const int r = row0 + tile_block(wm, mi) * 32 + (lane & 31);
     if (r >= row_end) return;
     bf16_t* crow = c + (size_t)r * N;
     const int col0 = n0 + wn * (BNO / WN) + ni * 32 + (lane >> 5) * 4;
@@ -235,8 +260,10 @@ __device__ __forceinline__ void decode_tile(const SlotTable& t, int S, int n_til
     const int tiles = __builtin_amdgcn_readlane(t.tiles, slot);
     int mt;
     tile_in_slot(rem, tiles, n_tiles, mt, nt);
-    row0 = __builtin_amdgcn_readlane(t.begin, slot) + mt * BM;
-    row_end = __builtin_amdgcn_readlane(t.end, slot);
+    const int b = __builtin_amdgcn_readlane(t.begin, slot), e = __builtin_amdgcn_readlane(t.end, slot);
+    const int rpt = rows_per_tile(e - b, tiles);
+    row0 = b + mt * rpt;
+    row_end = row0 + rpt < e ? row0 + rpt : e;
 }
 
 // Reads one accumulator where it lives (an AGPR).  Written out as an instruction so that the compiler
@@ -259,15 +286,17 @@ __device__ __forceinline__ float acc_read(float a) {
 template <int EPI>
 __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c, char* lds, int row0,
                                          int row_end, int n0, int N, int wm, int wn, int wave, int lane) {
+    const int my_blocks = blocks_of_wavefront(row0, row_end, wm);
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
     constexpr int ROWB = BNO * 2;      // bytes per image row
     constexpr int CPR = ROWB / 16;     // 16-byte chunks per image row
 #pragma unroll
     for (int mi = 0; mi < TB; ++mi) {
-        const int r = wm * 128 + mi * 32 + (lane & 31);  // token row of the tile
+        const int r = tile_block(wm, mi) * 32 + (lane & 31);  // token row of the tile
 #pragma unroll
         for (int ni = 0; ni < NB; ++ni) {
+            if (mi >= my_blocks) continue;  // no rows there: nothing was accumulated, nothing is stored
             const floatx16& gate = acc[ni][mi];
             const floatx16& up = acc[EPI == kSwiglu ? ni + NB : ni][mi];
 #pragma unroll
@@ -334,7 +363,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
     const bf16_t* wsel = (EPI == kSwiglu && wave >= NW / 2) ? b1 : b0;  // upper wavefronts load the W3 half
     const int f_row = lane & 31;
     const int f_sw = (((lane >> 5) ^ ((f_row >> 1) & 7)) & 7) * 16;
-    const int x_off = (wm * 128 + f_row) * ROW_BYTES + f_sw;  // + i * 32 rows
+    const int x_off = (tile_block(wm, 0) * 32 + f_row) * ROW_BYTES + f_sw;  // token block 0 of this wavefront; block i: tile_block(wm, i)
     int w_off[WB];  // SwiGLU: weight blocks 0..WB/2-1 are gate rows, WB/2..WB-1 the matching up rows
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
@@ -409,31 +438,52 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
         bf16x8 xf[2][TB], wf[2][WB];
+        // Everything that touches the matrix cores is compiled for NB = 0 .. TB token blocks: the number
+        // of this wavefront's 32-row blocks that hold rows of the tile (a ragged or evenly cut tile holds
+        // fewer than 256 rows).  NB = TB is the full tile, NB = 0 a wavefront that only takes part in the
+        // loads and barriers.
         // fragments of MFMA K-step kk of the tile whose token rows sit in ring slot sx and weight rows in sw
-        auto load_frags = [&](int buf, int sx, int sw, int kk) {
+        auto load_frags = [&](auto nb_c, int buf, int sx, int sw, int kk) {
+            constexpr int NB = decltype(nb_c)::value;
+            if (NB == 0) return;
             const char* xb = lds + sx * TILE_BYTES;
             const char* wb = lds + sw * TILE_BYTES;
 #pragma unroll
-            for (int i = 0; i < TB; ++i)
-                xf[buf][i] = *reinterpret_cast<const bf16x8*>(xb + ((x_off + i * 32 * ROW_BYTES) ^ (kk * 32)));
+            for (int i = 0; i < NB; ++i)
+                xf[buf][i] = *reinterpret_cast<const bf16x8*>(xb + ((x_off + tile_block(0, i) * 32 * ROW_BYTES) ^ (kk * 32)));
 #pragma unroll
             for (int i = 0; i < WB; ++i) wf[buf][i] = *reinterpret_cast<const bf16x8*>(wb + (w_off[i] ^ (kk * 32)));
         };
-        auto mfma_step = [&](int buf) {
+        auto mfma_step = [&](auto nb_c, int buf) {
+            constexpr int NB = decltype(nb_c)::value;
 #pragma unroll
             for (int ni = 0; ni < WB; ++ni)
 #pragma unroll
-                for (int mi = 0; mi < TB; ++mi)
+                for (int mi = 0; mi < NB; ++mi)
                     acc[ni][mi] =
                         __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
         };
-        // the step's MFMAs with its LDS reads and `loads` global->LDS loads slotted in one at a time
-        auto interleave = [&](int loads) {
+        // the step's MFMAs with its LDS reads and LOADS global->LDS loads slotted in between, so that no
+        // memory instruction waits in a full queue while the matrix pipe idles
+        auto interleave = [&](auto nb_c, auto loads_c) {
+            constexpr int NB = decltype(nb_c)::value;
+            constexpr int LOADS = decltype(loads_c)::value;
+            if constexpr (NB == TB) {
 #pragma unroll
-            for (int i = 0; i < TB * WB; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
-                if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one DS read
-                else if (i < TB + WB + loads) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
+                for (int i = 0; i < TB * WB; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
+                    if (i < TB + WB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one DS read
+                    else if (i < TB + WB + LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // one VMEM
+                }
+            } else if constexpr (NB > 0) {  // fewer MFMAs than memory instructions: several of those per MFMA
+                constexpr int MF = NB * WB;
+                constexpr int DS_PER = (NB + WB + MF - 1) / MF, VM_PER = (LOADS + MF - 1) / MF;
+#pragma unroll
+                for (int i = 0; i < MF; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);
+                    if (VM_PER > 0) __builtin_amdgcn_sched_group_barrier(0x010, VM_PER, 0);
+                }
             }
         };
 
@@ -448,8 +498,6 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             for (int i = 0; i < LPW; ++i) issue_load(false, i, 2 * t + 1, t);
         }
         barrier_keep_loads<2 * LPW>();
-        load_frags(0, 0, 1, 0);
-        __builtin_amdgcn_sched_barrier(0);
 
         // ---- main loop -----------------------------------------------------------------------------
         // Per K tile: four MFMA steps of 16.  Token rows of tile t+2 are requested during steps 0 and 1
@@ -457,54 +505,60 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // (into the slot of this tile's token rows, dead after the barrier).  One barrier per tile,
         // before step 3: by then every wavefront has read its last fragments of tile t, and tile t+1
         // has landed once only the 8 newest loads (token rows of t+2) are pending.
-        // A wavefront whose 128 token rows all lie past the slot's end (a ragged last tile) takes part
-        // in the loads and barriers but skips its fragment reads and MFMAs: the kernel runs at the
-        // chip's power limit, so work not done is speed for the others.
-        auto k_loop = [&](auto idle_tag) {
-            constexpr bool IDLE = decltype(idle_tag)::value;
+        // A wavefront skips the fragment reads and MFMAs of its token blocks without rows: the kernel
+        // runs at the chip's power limit, so work not done is speed for the others.
+        auto k_loop = [&](auto nb_c) {
+            constexpr bool IDLE = decltype(nb_c)::value == 0;
+            load_frags(nb_c, 0, 0, 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
             int sx = 0;  // ring slot of tile t's token rows
             for (int t = 0; t < k_tiles; ++t) {
                 const int sw = sx + 1 >= SLOTS ? sx + 1 - SLOTS : sx + 1;   // this tile's weight rows
                 const int sx1 = sx + 2 >= SLOTS ? sx + 2 - SLOTS : sx + 2;  // next tile's token rows
                 const int sw1 = sx + 3 >= SLOTS ? sx + 3 - SLOTS : sx + 3;  // next tile's weight rows
                 const int sx2 = sx + 4 >= SLOTS ? sx + 4 - SLOTS : sx + 4;  // token rows of t+2 (held weights of t-1)
-                if (!IDLE) load_frags(1, sx, sw, 1);
+                load_frags(nb_c, 1, sx, sw, 1);
 #pragma unroll
                 for (int i = 0; i < LPW / 2; ++i) issue_load(true, i, sx2, t + 2);
                 if (!IDLE) {
-                    mfma_step(0);
-                    interleave(LPW / 2);
+                    mfma_step(nb_c, 0);
+                    interleave(nb_c, std::integral_constant<int, LPW / 2>{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (!IDLE) load_frags(0, sx, sw, 2);
+                load_frags(nb_c, 0, sx, sw, 2);
 #pragma unroll
                 for (int i = LPW / 2; i < LPW; ++i) issue_load(true, i, sx2, t + 2);
                 if (!IDLE) {
-                    mfma_step(1);
-                    interleave(LPW / 2);
+                    mfma_step(nb_c, 1);
+                    interleave(nb_c, std::integral_constant<int, LPW / 2>{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (!IDLE) {
-                    load_frags(1, sx, sw, 3);
-                    mfma_step(0);
-                    interleave(0);
+                    load_frags(nb_c, 1, sx, sw, 3);
+                    mfma_step(nb_c, 0);
+                    interleave(nb_c, std::integral_constant<int, 0>{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 barrier_keep_loads<LPW>();
                 __builtin_amdgcn_sched_barrier(0);
-                if (!IDLE) load_frags(0, sx1, sw1, 0);
+                load_frags(nb_c, 0, sx1, sw1, 0);
 #pragma unroll
                 for (int i = 0; i < LPW; ++i) issue_load(false, i, sx, t + 2);  // weight rows of t+2 over this tile's token rows
                 if (!IDLE) {
-                    mfma_step(1);
-                    interleave(LPW);
+                    mfma_step(nb_c, 1);
+                    interleave(nb_c, std::integral_constant<int, LPW>{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 sx = sx1;
             }
         };
-        if (row0 + wm * 128 >= row_end) k_loop(std::true_type{});
-        else k_loop(std::false_type{});
+        const int my_blocks = blocks_of_wavefront(row0, row_end, wm);
+        static_assert(TB == 4, "written out for four token blocks per wavefront");
+        if (my_blocks >= 4) k_loop(std::integral_constant<int, 4>{});
+        else if (my_blocks == 3) k_loop(std::integral_constant<int, 3>{});
+        else if (my_blocks == 2) k_loop(std::integral_constant<int, 2>{});
+        else if (my_blocks == 1) k_loop(std::integral_constant<int, 1>{});
+        else k_loop(std::integral_constant<int, 0>{});
         // surplus loads must not land in the next trip's tiles (or outlive the workgroup's LDS)
         barrier_keep_loads<0>();
 

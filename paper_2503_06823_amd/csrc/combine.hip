@@ -51,20 +51,40 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
     for (long long u = wave; u < units; u += n_waves) {
         const int t = (int)(u / chunks);
         const int c = (int)(u % chunks) * 64 * N + lane * N;
-        if (c >= d) continue;
+        // lane j fetches the row number and the weight of the token's j-th expert (k <= 64), so that the
+        // rows' addresses are known at once and their loads go out together instead of one dependent
+        // pair of loads per expert
+        int my_r = -1;
+        float my_w = 0.0f;
+        if (lane < k) {
+            my_r = inv_perm[(size_t)t * k + lane];
+            my_w = topk_weight[(size_t)t * k + lane];
+        }
         float acc[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) acc[i] = 0.0f;
-        for (int j = 0; j < k; ++j) {
-            const int r = inv_perm[(size_t)t * k + j];
-            if (r < 0) continue;
-            const float w = topk_weight[(size_t)t * k + j];
-            float v[N];
-            Pack<T>::load(y_perm + (size_t)r * d + c, v);
+        for (int j0 = 0; j0 < k; j0 += 4) {  // four rows in flight, added in ascending j
+            float v[4][N];
+            float w[4];
 #pragma unroll
-            for (int i = 0; i < N; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+            for (int jj = 0; jj < 4; ++jj) {
+                const int j = j0 + jj < k ? j0 + jj : k - 1;
+                const int r = __builtin_amdgcn_readlane(my_r, j);
+                const bool ok = j0 + jj < k && r >= 0;  // r < 0: an assignment the permutation left out
+                w[jj] = ok ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), j)) : 0.0f;
+#pragma unroll
+                for (int i = 0; i < N; ++i) v[jj][i] = 0.0f;
+                if (ok && c < d) Pack<T>::load(y_perm + (size_t)r * d + c, v[jj]);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                if (j0 + jj < k) {
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[i] = fmaf(w[jj], v[jj][i], acc[i]);
+                }
+            }
         }
-        Pack<T>::store(out + (size_t)t * d + c, acc);
+        if (c < d) Pack<T>::store(out + (size_t)t * d + c, acc);
     }
 }
 

@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("name,kw", [
     ("graph_decode", dict(T=64, d_model=512, d_ff=1088, E=8, k=2, R=6)),          # streaming FFN path
     ("graph_prefill", dict(T=700, d_model=328, d_ff=456, E=8, k=2, R=4)),         # tiled FFN path with split tiles
+    ("graph_one_prompt", dict(T=190, d_model=328, d_ff=456, E=8, k=2, R=4)),      # 128-row-tile FFN path
 ])
 def test_graph_replays_match_eager(gpu_device, name, kw):
     c = gen.LayerConfig(name=name, index=110, dtype="bf16", act="swiglu", **kw)

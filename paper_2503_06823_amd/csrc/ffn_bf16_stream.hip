@@ -124,9 +124,10 @@ __global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const 
             const int tr = (LX * wave + i) * RPI + l_rin;  // row of the token tile
             x_chunk[i] = l_pos ^ (tr & 15);
             int r = tok0 + tr;
-            r = r < row_end ? r : row_end - 1;
+            const bool past = r >= row_end;  // rows past the slot's end: out of range, zeros without memory traffic
+            r = past ? row_end - 1 : r;
             if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
-            x_voff[i] = ((uint32_t)r * (uint32_t)K + x_chunk[i] * 8) * 2u;
+            x_voff[i] = past ? a_bytes : ((uint32_t)r * (uint32_t)K + x_chunk[i] * 8) * 2u;
         }
         auto issue_tile = [&](int stage, int k0) {
             char* base = lds + stage * STAGE_BYTES;

@@ -40,6 +40,8 @@ constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per tile row
 constexpr int RPI = 1024 / ROW_BYTES;       // tile rows filled by one load instruction
 constexpr int SPW = BK / 16 / 4;            // MFMA steps per wavefront and tile
 constexpr int LX = X_BYTES / 1024 / 4;      // token load instructions per wavefront and tile
+// cache policy of the weight loads: every weight byte is read once per launch (non-temporal: bit 1 of the aux operand)
+constexpr int kStreamOnce = 2;
 constexpr unsigned kRotation = 21;           // K-tile rotation per workgroup (measured best of 1..29)
 constexpr int RED_BYTES = 3 * 32 * 64 * 4;  // partial sums of wavefronts 1..3
 static_assert(RED_BYTES <= STAGES * (32 * ROW_BYTES + X_BYTES), "the reduction reuses the tile stages");
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const 
                 uint32_t v = w_voff[i];
                 if (KTAIL && k0 + w_chunk[i] * 8 >= K) v = b_bytes;  // out of range: zeros
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_void*)(base + (LW * wave + i) * 1024), 16, (int)v,
-                                                         k0 * 2, 0, 0);
+                                                         k0 * 2, 0, kStreamOnce);
             }
 #pragma unroll
             for (int i = 0; i < LX; ++i) {

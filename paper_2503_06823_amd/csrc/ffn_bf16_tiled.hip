@@ -137,6 +137,7 @@ __device__ __forceinline__ Plan make_plan(int tiles, int k_tiles, int G) {
 // (12 panels for 32 tiles; m fastest over a whole tall slot would need up to 33).
 // rem = number of the tile within the slot -> its m-tile and n-tile.
 constexpr int kBlockM = 8, kBlockN = 4;
+constexpr int kSkipBlocksUpToTiles = 4;  // see the K loop's dispatch
 __device__ __forceinline__ void tile_in_slot(int rem, int m_tiles, int n_tiles, int& mt, int& nt) {
     const int group = rem / (m_tiles * kBlockN);  // group of up to four n-tiles
     const int gn = n_tiles - group * kBlockN < kBlockN ? n_tiles - group * kBlockN : kBlockN;
@@ -251,7 +252,7 @@ __device__ __forceinline__ SlotTable make_slot_table(const int32_t* __restrict__
 }
 
 __device__ __forceinline__ void decode_tile(const SlotTable& t, int S, int n_tiles, int lane, int L, int& slot,
-                                            int& row0, int& row_end, int& nt) {
+                                            int& row0, int& row_end, int& nt, int& slot_tiles) {
     // slots are in tile order and an empty slot starts where its successor does: the last slot that
     // starts at or before L is the non-empty one that holds it
     const unsigned long long m = __ballot(lane < S && t.first <= L);
@@ -264,6 +265,7 @@ __device__ __forceinline__ void decode_tile(const SlotTable& t, int S, int n_til
     const int rpt = rows_per_tile(e - b, tiles);
     row0 = b + mt * rpt;
     row_end = row0 + rpt < e ? row0 + rpt : e;
+    slot_tiles = tiles;
 }
 
 // Reads one accumulator where it lives (an AGPR).  Written out as an instruction so that the compiler
@@ -286,7 +288,6 @@ __device__ __forceinline__ float acc_read(float a) {
 template <int EPI>
 __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c, char* lds, int row0,
                                          int row_end, int n0, int N, int wm, int wn, int wave, int lane) {
-    const int my_blocks = blocks_of_wavefront(row0, row_end, wm);
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
     constexpr int ROWB = BNO * 2;      // bytes per image row
@@ -296,7 +297,6 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __rest
         const int r = tile_block(wm, mi) * 32 + (lane & 31);  // token row of the tile
 #pragma unroll
         for (int ni = 0; ni < NB; ++ni) {
-            if (mi >= my_blocks) continue;  // no rows there: nothing was accumulated, nothing is stored
             const floatx16& gate = acc[ni][mi];
             const floatx16& up = acc[EPI == kSwiglu ? ni + NB : ni][mi];
 #pragma unroll
@@ -390,8 +390,8 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 piece = sk_item;
             }
         }
-        int slot, row0, row_end, nt;
-        decode_tile(table, S, n_tiles, lane, L, slot, row0, row_end, nt);
+        int slot, row0, row_end, nt, slot_tiles;
+        decode_tile(table, S, n_tiles, lane, L, slot, row0, row_end, nt, slot_tiles);
         const int n0 = nt * BNO;
 
         // ---- global -> LDS -------------------------------------------------------------------------
@@ -552,7 +552,12 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 sx = sx1;
             }
         };
-        const int my_blocks = blocks_of_wavefront(row0, row_end, wm);
+        // Blocks without rows are skipped only in slots of a few tiles, where a tile's padding is a large
+        // share of the slot's matrix work.  In a tall slot the one ragged tile multiplies its padding: the
+        // 32 workgroups of an XCD share operand panels through L2 only while they walk K in step, and a
+        // tile that finishes early falls out of step for good (Mixtral prefill: 20 % more bytes fetched
+        // from beyond L2 when the ragged tiles are cut short).
+        const int my_blocks = slot_tiles > kSkipBlocksUpToTiles ? TB : blocks_of_wavefront(row0, row_end, wm);
         static_assert(TB == 4, "written out for four token blocks per wavefront");
         if (my_blocks >= 4) k_loop(std::integral_constant<int, 4>{});
         else if (my_blocks == 3) k_loop(std::integral_constant<int, 3>{});

@@ -428,6 +428,15 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
             char* dst = lds + rs * TILE_BYTES + (LPW * wave + i) * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(tok ? a_rsrc : b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 0);
         };
+        // the same for a weight tile whose bytes no other tile reads (a slot of one m-tile): non-temporal hint
+        auto issue_weights_once = [&](int i, int rs, int tk) {
+            int k0 = k_first + tk * BK;
+            k0 = k0 < k_last ? k0 : k_last;
+            uint32_t voff = b_voff[i];
+            if ((KTAIL && k0 + chunk[i] * 8 >= K) || tk >= k_tiles) voff = b_bytes;
+            char* dst = lds + rs * TILE_BYTES + (LPW * wave + i) * 1024;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_void*)dst, 16, (int)voff, k0 * 2, 0, 2);
+        };
 
         floatx16 acc[WB][TB];  // [weight block][token block]
 #pragma unroll
@@ -507,7 +516,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // has landed once only the 8 newest loads (token rows of t+2) are pending.
         // A wavefront skips the fragment reads and MFMAs of its token blocks without rows: the kernel
         // runs at the chip's power limit, so work not done is speed for the others.
-        auto k_loop = [&](auto nb_c) {
+        auto k_loop = [&](auto nb_c, auto once_c) {
             constexpr bool IDLE = decltype(nb_c)::value == 0;
             load_frags(nb_c, 0, 0, 1, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -543,7 +552,10 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 __builtin_amdgcn_sched_barrier(0);
                 load_frags(nb_c, 0, sx1, sw1, 0);
 #pragma unroll
-                for (int i = 0; i < LPW; ++i) issue_load(false, i, sx, t + 2);  // weight rows of t+2 over this tile's token rows
+                for (int i = 0; i < LPW; ++i) {  // weight rows of t+2 over this tile's token rows
+                    if (decltype(once_c)::value) issue_weights_once(i, sx, t + 2);
+                    else issue_load(false, i, sx, t + 2);
+                }
                 if (!IDLE) {
                     mfma_step(nb_c, 1);
                     interleave(nb_c, std::integral_constant<int, LPW>{});
@@ -559,11 +571,21 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // from beyond L2 when the ragged tiles are cut short).
         const int my_blocks = slot_tiles > kSkipBlocksUpToTiles ? TB : blocks_of_wavefront(row0, row_end, wm);
         static_assert(TB == 4, "written out for four token blocks per wavefront");
-        if (my_blocks >= 4) k_loop(std::integral_constant<int, 4>{});
-        else if (my_blocks == 3) k_loop(std::integral_constant<int, 3>{});
-        else if (my_blocks == 2) k_loop(std::integral_constant<int, 2>{});
-        else if (my_blocks == 1) k_loop(std::integral_constant<int, 1>{});
-        else k_loop(std::integral_constant<int, 0>{});
+        // A slot of one m-tile: nobody else reads its weight panel, which is then loaded with the
+        // non-temporal hint, so that the stream does not push the token rows out of the caches.
+        if (slot_tiles == 1) {
+            if (my_blocks >= 4) k_loop(std::integral_constant<int, 4>{}, std::true_type{});
+            else if (my_blocks == 3) k_loop(std::integral_constant<int, 3>{}, std::true_type{});
+            else if (my_blocks == 2) k_loop(std::integral_constant<int, 2>{}, std::true_type{});
+            else if (my_blocks == 1) k_loop(std::integral_constant<int, 1>{}, std::true_type{});
+            else k_loop(std::integral_constant<int, 0>{}, std::true_type{});
+        } else {
+            if (my_blocks >= 4) k_loop(std::integral_constant<int, 4>{}, std::false_type{});
+            else if (my_blocks == 3) k_loop(std::integral_constant<int, 3>{}, std::false_type{});
+            else if (my_blocks == 2) k_loop(std::integral_constant<int, 2>{}, std::false_type{});
+            else if (my_blocks == 1) k_loop(std::integral_constant<int, 1>{}, std::false_type{});
+            else k_loop(std::integral_constant<int, 0>{}, std::false_type{});
+        }
         // surplus loads must not land in the next trip's tiles (or outlive the workgroup's LDS)
         barrier_keep_loads<0>();
 

@@ -54,9 +54,9 @@ FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
 // at the Mixtral shape 369 us against the tiled kernels' 477 us with 21 rows per slot, but 661 us
 // against 477 us with 42; random routing at 28 rows per slot on average puts about one slot in
 // five over 32 rows.  Up to kMidRowsPerSlot rows per slot the tiles of 128 token rows are used:
-// they keep more weight bytes in flight (Mixtral shape, 8 slots: 526 us against the large tiles'
-// 602 us at 32 rows per slot, 542 against 615 us at 96), but lose once many slots need a second
-// tile (128 rows per slot: 727 against 632 us).
+// their variant with 128 weight rows per tile runs the second product faster (Mixtral shape, 8
+// slots, whole FFN: 522 us against the large tiles' 538 us at 64 rows per slot, 539 against 552 us
+// at 96), but they lose once many slots need a second tile (128 rows per slot: 723 against 563 us).
 constexpr long long kStreamRowsPerSlot = 28;
 constexpr long long kMidRowsPerSlot = 100;
 FfnPath ffn_bf16_path(const emoe_layer_desc& d) {

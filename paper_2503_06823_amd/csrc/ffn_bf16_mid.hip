@@ -54,6 +54,7 @@ constexpr int TB = 2;                      // 32-token blocks per wavefront
 constexpr int LX = BM / 8 / NW;            // token load instructions per wavefront and K tile (4)
 constexpr int XCDS = 8;
 constexpr int kCUs = 256;
+constexpr unsigned kRotation = 21;          // K-tile rotation per slot (best of 5, 21, 37 and an even spread)
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
 
@@ -152,19 +153,30 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(wsel + (size_t)slot * N * K), 0, (int)b_bytes, 0x00020000);
     const int k_tiles = (K + BK - 1) / BK;
     const int k_last = (k_tiles - 1) * BK;
+    // Every tile walks all of K, but the tiles of different slots start at different K tiles: started
+    // together, all workgroups would read the same 128-byte column of rows a power of two apart at the
+    // same time, which lands on few memory channels (second product of a layer with d_ff = 8192: 127
+    // -> 100 us).  The tiles of one slot share the start: they stay in step, so their common token rows
+    // and the weight panel common to its m-tiles are fetched once.  A step per n-tile as well costs up to
+    // 15 % once the slot's token rows no longer stay in L2 beside the weight stream.
+    const int k_rot = (int)(((unsigned)slot * kRotation) % (unsigned)k_tiles);
+    auto k_of = [&](int tk) {
+        int kk = tk + k_rot;
+        kk = kk >= k_tiles ? kk - k_tiles : kk;
+        const int k0 = kk * BK;
+        return k0 < k_last ? k0 : k_last;
+    };
     // K tile number tk into stage st.  Past the last tile the loads go on (no branches in the loop)
     // but out of range: zeros land in a stage that nobody reads any more.
     auto issue_x = [&](int i, int st, int tk) {
-        int k0 = tk * BK;
-        k0 = k0 < k_last ? k0 : k_last;
+        const int k0 = k_of(tk);
         uint32_t v = x_voff[i];
         if ((KTAIL && k0 + x_chunk[i] * 8 >= K) || tk >= k_tiles) v = a_bytes;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void*)(lds + st * STAGE_BYTES + (LX * wave + i) * 1024), 16,
                                                  (int)v, k0 * 2, 0, 0);
     };
     auto issue_w = [&](int i, int st, int tk) {
-        int k0 = tk * BK;
-        k0 = k0 < k_last ? k0 : k_last;
+        const int k0 = k_of(tk);
         uint32_t v = w_voff[i];
         if ((KTAIL && k0 + w_chunk[i] * 8 >= K) || tk >= k_tiles) v = b_bytes;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc,

@@ -74,6 +74,7 @@ constexpr int kPersistentGroups = 256;  // one workgroup per CU
 constexpr int kMaxSplits = 8;           // K pieces per leftover tile, at most
 constexpr int kFixupGroups = 255 * 16;  // workgroups of the fix-up launch: the most units there can be
 constexpr int kPlanFloats = kTiledPlanBytes / 4;  // the plan sits ahead of the partial sums
+constexpr unsigned kRotation = 21;  // K-tile rotation per slot
 constexpr int NW = 4;            // wavefronts per workgroup, arranged 2 (tokens) x NW/2 (weight rows)
 constexpr int WN = NW / 2;
 constexpr int TB = 4;            // 32-token blocks per wavefront (128 tokens)
@@ -106,7 +107,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // The launch is persistent: one workgroup per CU.  Output tiles are numbered in (slot, n-tile,
 // m-tile) order of tile_in_slot.  The first `rounds * G` tiles are dealt out whole, `rounds` per
 // workgroup, so that the 32 workgroups of an XCD hold 32 consecutive tiles at any time (one weight
-// panel and the slot's token panels stay in that XCD's L2).  The `left` tiles that do not fill a
+// panel and the slot's token panels stay in that XCD's L2).  Round r covers tiles r*G .. (r+1)*G-1,
+// 32 for each XCD: every XCD works its way through all slots, so slots whose tiles cost less (fewer
+// rows than a tile holds) do not leave some XCDs idle while others still work (a contiguous range of
+// tiles per XCD took 4-7 % longer at 250-500 rows per slot).  The `left` tiles that do not fill a
 // round are split along K into `splits` pieces each, so that they too occupy (nearly) every CU: a
 // piece writes its fp32 accumulators to the workspace and a small second kernel adds the pieces in
 // order and applies the epilogue.  Everything is derived from slot_offsets on the device.
@@ -379,7 +383,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // ---- what to do in this trip -------------------------------------------------------------
         int L, kb = 0, ke = k_tiles_all, piece = -1;
         if (item < plan.rounds) {
-            L = xcd * plan.rounds * per_xcd + item * per_xcd + cu;
+            L = item * G + xcd * per_xcd + cu;
         } else {
             if (sk_item >= plan.left * plan.splits) break;
             L = plan.rounds * G + sk_item / plan.splits;
@@ -419,9 +423,18 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // one load instruction i of the token (tok) or weight tile of K tile number tk, into ring slot rs.
         // Near the end of K the loads go on (the loop body stays free of branches) but out of range:
         // zeros land in a slot that nobody reads any more.
+        // The tiles of different slots start at different K tiles of their range (all workgroups on the
+        // same 128-byte column of rows a power of two apart land on few memory channels); the tiles of a
+        // slot share the start and so stay in step.  The order is a fixed function of the tile.
+        const int k_rot = (int)(((unsigned)slot * kRotation) % (unsigned)k_tiles);
+        auto k_of = [&](int tk) {
+            int kk = tk + k_rot;
+            kk = kk >= k_tiles ? kk - k_tiles : kk;
+            const int k0 = k_first + kk * BK;
+            return k0 < k_last ? k0 : k_last;
+        };
         auto issue_load = [&](bool tok, int i, int rs, int tk) {
-            int k0 = k_first + tk * BK;
-            k0 = k0 < k_last ? k0 : k_last;
+            const int k0 = k_of(tk);
             uint32_t voff = tok ? a_voff[i] : b_voff[i];
             // out of range (zeros arrive, memory is not touched): chunks past K, and the loads past the last tile
             if ((KTAIL && k0 + chunk[i] * 8 >= K) || tk >= k_tiles) voff = tok ? a_bytes : b_bytes;
@@ -430,8 +443,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         };
         // the same for a weight tile whose bytes no other tile reads (a slot of one m-tile): non-temporal hint
         auto issue_weights_once = [&](int i, int rs, int tk) {
-            int k0 = k_first + tk * BK;
-            k0 = k0 < k_last ? k0 : k_last;
+            const int k0 = k_of(tk);
             uint32_t voff = b_voff[i];
             if ((KTAIL && k0 + chunk[i] * 8 >= K) || tk >= k_tiles) voff = b_bytes;
             char* dst = lds + rs * TILE_BYTES + (LPW * wave + i) * 1024;

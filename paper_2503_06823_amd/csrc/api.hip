@@ -45,6 +45,7 @@ FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
     w.partials = align256((A > 0 ? A : 1) * d.d_ff * elem_bytes(d));
     w.total = w.partials;
     if (d.dtype == EMOE_BF16 && ffn_bf16_path(d) == kFfnTiled) w.total += kTiledPartialBytes;
+    if (d.dtype == EMOE_BF16 && ffn_bf16_path(d) == kFfnMid) w.total += kMidPartialBytes;
     return w;
 }
 

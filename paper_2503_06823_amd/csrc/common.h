@@ -35,11 +35,12 @@ struct PermuteWs {
 };
 struct FfnWs {
     size_t h;         // dtype [A][f]
-    size_t partials;  // fp32 K pieces of leftover tiles (tiled bf16 path only, else 0 bytes)
+    size_t partials;  // fp32 K pieces of tiles cut along K (the two tiled bf16 paths, else 0 bytes)
     size_t total;
 };
 constexpr size_t kTiledPlanBytes = 256;  // the tiled kernel leaves its work plan here for the fix-up kernel
 constexpr size_t kTiledPartialBytes = kTiledPlanBytes + (size_t)256 * 256 * 256 * sizeof(float);  // + 256 pieces of a 256x256 tile
+constexpr size_t kMidPartialBytes = (size_t)512 * 128 * 128 * sizeof(float);  // the 128-row-tile kernel: two pieces of a 128x128 tile per CU
 constexpr int kPermuteChunk = 1024;  // assignments per workgroup in the counting sort
 PermuteWs permute_ws_layout(const emoe_layer_desc& d);
 FfnWs ffn_ws_layout(const emoe_layer_desc& d);

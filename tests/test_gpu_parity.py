@@ -35,6 +35,13 @@ SMALL_CASES = [
     cfg("mid_relu_wide_ff", act="relu", T=1500, d_model=72, d_ff=2560, E=64, k=1, R=16, zipf_s=1.1, index=66),
     cfg("mid_swiglu_wide_ff", T=800, d_model=72, d_ff=1408, E=16, k=2, R=16, index=67),
     cfg("mid_few_rows_per_slot", T=100, d_model=192, d_ff=264, E=8, k=2, R=5, index=60),
+    # a long K and fewer 128 x 128 tiles than CUs: the persistent launch cuts the tiles along K and a second kernel
+    # adds the pieces (first product: K = 4104 with a K tail; second product: K = 4160)
+    cfg("mid_cut_first_product", T=100, d_model=4104, d_ff=264, E=8, k=2, R=3, index=68),
+    cfg("mid_cut_second_product", act="relu", T=240, d_model=200, d_ff=4160, E=8, k=1, R=4, index=69),
+    # a long K and about as many tiles as CUs, or more: the persistent launch takes whole tiles, one or two each
+    cfg("mid_persistent_whole_tiles", T=300, d_model=4096, d_ff=1152, E=8, k=2, R=8, index=70),
+    cfg("mid_persistent_two_rounds", act="relu", T=1600, d_model=4096, d_ff=2048, E=64, k=1, R=16, zipf_s=1.1, index=71),
     # tiles of 256 token rows (A > 100 S): several M tiles + tail, N tails, K tail
     cfg("tiled_swiglu_ragged", T=1700, d_model=328, d_ff=456, E=8, k=2, R=4, index=61),
     cfg("tiled_swiglu_aligned", T=1024, d_model=512, d_ff=768, E=8, k=2, R=3, S=5, index=62),

@@ -383,9 +383,11 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
 #pragma unroll
             for (int i = 0; i < WB; ++i)
 #pragma unroll
-                for (int j = 0; j < TB; ++j)
+                for (int j = 0; j < TB; ++j) {
+                    if (row0 + wm * 64 + j * 32 >= row_end) continue;  // a block without rows: the second kernel skips it too
 #pragma unroll
                     for (int v = 0; v < 16; ++v) dst[((i * TB + j) * 16 + v) * (64 * NW)] = acc[i][j][v];
+                }
             continue;
         }
 
@@ -464,6 +466,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
     decode_tile(work, S, lane, tile, slot, row0, row_end, nt);
     for (int unit = 0; unit < UNITS; ++unit) {
         const int mi = unit / NB, ni = unit % NB;
+        if (row0 + wm * 64 + mi * 32 >= row_end) continue;  // this wavefront's block holds no rows: nothing was written
         floatx16 gate, up;
 #pragma unroll
         for (int v = 0; v < 16; ++v) { gate[v] = 0.0f; up[v] = 0.0f; }

@@ -608,9 +608,11 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
 #pragma unroll
             for (int i = 0; i < WB; ++i)
 #pragma unroll
-                for (int j = 0; j < TB; ++j)
+                for (int j = 0; j < TB; ++j) {
+                    if (row0 + tile_block(wm, j) * 32 >= row_end) continue;  // a block without rows: the fix-up skips it too
 #pragma unroll
                     for (int v = 0; v < 16; ++v) dst[((i * TB + j) * 16 + v) * (64 * NW)] = acc_read(acc[i][j][v]);
+                }
         }
     }
 }
@@ -638,6 +640,7 @@ __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restric
     const int mi = unit / NB, ni = unit % NB;
     int slot, row0, row_end, nt;
     decode_tile(offsets, S, n_tiles, plan.rounds * G + tile, slot, row0, row_end, nt);
+    if (row0 + tile_block(wave / WN, mi) * 32 >= row_end) return;  // this wavefront's block holds no rows: nothing was written
     floatx16 gate, up;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { gate[v] = 0.0f; up[v] = 0.0f; }

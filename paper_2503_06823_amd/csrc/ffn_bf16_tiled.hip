@@ -480,9 +480,11 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
 #pragma unroll
             for (int ni = 0; ni < WB; ++ni)
 #pragma unroll
-                for (int mi = 0; mi < NB; ++mi)
+                for (int m = 0; m < NB; ++m) {
+                    const int mi = (ni & 1) ? NB - 1 - m : m;  // back and forth: only one operand changes between two MFMAs
                     acc[ni][mi] =
                         __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][ni], xf[buf][mi], acc[ni][mi], 0, 0, 0);
+                }
         };
         // the step's MFMAs with its LDS reads and LOADS global->LDS loads slotted in between, so that no
         // memory instruction waits in a full queue while the matrix pipe idles

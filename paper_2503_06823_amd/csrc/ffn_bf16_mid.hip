@@ -32,14 +32,16 @@
 //  - Tiles of 256 weight rows: one workgroup per output tile, not persistent (tiles are short, at most
 //    64 K tiles of half the work of the large kernel's, and the hardware's dispatcher balances
 //    them); the launch covers an upper bound of tiles and surplus workgroups exit.
-//  - Tiles of 128 weight rows (taken when there are at most about as many tiles as CUs): a persistent
-//    launch, one workgroup per CU.  With clearly fewer tiles than CUs (six slots of one m-tile at the
-//    Mixtral shape: 192) a workgroup per tile would leave CUs idle while the others each walk a long
-//    K; instead all tiles' K tiles, in tile order, form one sequence that is cut into equal
+//  - Tiles of 128 weight rows (five stages; taken when tiles of 256 would number no more than the
+//    CUs): the same with a short K; with a long one (64 K tiles or more) a persistent launch, one
+//    workgroup per CU.  With clearly fewer tiles than CUs (a decode batch over two resident experts
+//    at the Mixtral shape: 64) a workgroup per tile would leave CUs idle while the others each walk
+//    a long K; instead all tiles' K tiles, in tile order, form one sequence that is cut into equal
 //    consecutive shares, one per workgroup.  A share covers the end of one tile and the start of
 //    the next: each piece leaves its fp32 accumulators in the workspace, and a second kernel adds
-//    the pieces of a tile in K order (deterministic) and applies the epilogue.  With about as many
-//    tiles as CUs or more, the workgroups take whole tiles and nothing is cut.
+//    the pieces of a tile in K order (deterministic) and applies the epilogue.  That is done only
+//    when it spares every workgroup a walk of 48 K tiles: the pieces are extra traffic.  Otherwise
+//    the workgroups take whole tiles and nothing is cut.
 #include <atomic>
 #include <type_traits>
 

@@ -67,7 +67,8 @@ const char *emoe_status_string(int status);
  * h [A,f] in dtype plus, for bf16 layers with more than 28 rows per slot on average,
  * 32 or 64 MiB of fp32 partial sums of output tiles cut along K.  Neither workspace
  * needs initialising, and nothing in them outlives a call except h between the two
- * passes of emoe_expert_ffn_pass. */
+ * passes of emoe_expert_ffn_pass.  Calls that may run at the same time (different
+ * streams) need workspaces of their own. */
 int emoe_workspace_bytes(const emoe_layer_desc *desc, size_t *permute_ws_bytes, size_t *ffn_ws_bytes);
 
 /*

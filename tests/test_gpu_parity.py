@@ -185,6 +185,39 @@ def test_random_small_layers(gpu_device, c):
     dl.check_gather_path_is_identical()
 
 
+def _random_long_k_cases(n, seed):
+    """Seeded random layers with one long and one short product (K >= 64 tiles of 64 in one of them)
+    and 29-200 rows per slot: the persistent launch of the 128-row tiles, which cuts tiles along K
+    when they are few, takes whole tiles otherwise, and the 256-row tiles' K pieces beyond that."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        act = "relu" if rng.random() < 0.3 else "swiglu"
+        E = int(rng.choice([1, 2, 4, 8, 16]))
+        R = int(rng.integers(1, E + 1))
+        k = int(rng.integers(1, min(R, 4) + 1))
+        S = int(rng.integers(R, E + 1))
+        rows = int(rng.choice([29, 47, 64, 80, 100, 128, 200]))
+        T = max(1, rows * S // k)
+        big, small = int(rng.choice([4096, 4104, 4160, 6152])), int(rng.choice([64, 136, 264, 520]))
+        d_model, d_ff = (big, small) if i % 2 == 0 else (small, big)
+        cases.append(cfg(f"longk{i}_{act}_T{T}_d{d_model}_f{d_ff}_E{E}_k{k}_R{R}_S{S}", act=act, T=T, d_model=d_model,
+                         d_ff=d_ff, E=E, k=k, R=R, S=S, index=200 + i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_long_k_cases(12, 20250307), ids=lambda c: c.name)
+def test_random_layers_with_a_long_k(gpu_device, c):
+    inp = gen.make_layer_inputs(c, shuffle_slots=c.index % 2 == 1 and c.slots > 1)
+    ref = oracle.layer_forward(inp)
+    dl = DeviceLayer(inp)
+    dl.forward()
+    torch.cuda.synchronize()
+    check_routing_and_permutation(dl, ref)
+    check_outputs(dl, ref)
+    dl.check_gather_path_is_identical()
+
+
 @pytest.mark.parametrize("name", ["mid_swiglu_ragged", "tiled_relu_skewed", "stream_decode", "C1_tiny_f32"])
 def test_layer_forward_in_one_call_equals_the_four_calls(gpu_device, name):
     c = [c for c in SMALL_CASES if c.name == name][0]

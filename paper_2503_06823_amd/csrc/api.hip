@@ -60,10 +60,23 @@ FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
 // at 96), but they lose once many slots need a second tile (128 rows per slot: 723 against 563 us).
 constexpr long long kStreamRowsPerSlot = 28;
 constexpr long long kMidRowsPerSlot = 100;
+// A small layer (all resident slots' weights stream in some 60 us) is bound by how well its tiles
+// fill the chip, not by the weight stream, and around 256 rows per slot the 128-row tiles fill it
+// better: half the slots then need a second 256-row tile for a few rows.  Measured (FFN, us, 256-row
+// against 128-row tiles): d = 768, f = 3072, 16 slots of 214-291 rows 120 / 86; 32 slots of 195-315
+// rows 177 / 145; d = 2048, f = 1408, 8 slots of 182-206 rows 100 / 72; d = 2048, f = 8192, 2 slots
+// of 256 rows 134 / 102, 3 slots of 238-266 rows 172 / 148.  Below about 170 rows per slot the
+// 256-row tiles win or are level there too (16 slots of 99-148 rows: 104 / 123), and so they do at
+// any number of rows once the weights are large (Mixtral shape, 8 slots of 232-278 rows: 863 / 998).
+constexpr long long kSmallLayerWeightBytes = 320ll << 20;
+constexpr long long kSmallLayerMidFrom = 170, kSmallLayerMidTo = 300;  // rows per slot
 FfnPath ffn_bf16_path(const emoe_layer_desc& d) {
     const long long A = (long long)d.T * d.k;
     if (A <= kStreamRowsPerSlot * d.S) return kFfnStream;
     if (A <= kMidRowsPerSlot * d.S) return kFfnMid;
+    const long long weight_bytes = (long long)d.S * (d.act == EMOE_ACT_SWIGLU ? 3 : 2) * d.d_model * d.d_ff * 2;
+    if (weight_bytes <= kSmallLayerWeightBytes && A >= kSmallLayerMidFrom * d.S && A <= kSmallLayerMidTo * d.S)
+        return kFfnMid;
     return kFfnTiled;
 }
 

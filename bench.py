@@ -362,6 +362,10 @@ def main():
                                     "X3 one short prompt at the Mixtral-8x7B shape: T=256 d_model=4096 d_ff=14336 E=8 "
                                     "top-2 SwiGLU, 6 of 8 resident, bf16; 3 rotating copies of the slot buffers")
 
+        result["x4"] = other_config(torch, P, gen, gen.X4, 20, 5, 1,
+                                    "X4 two prompts of 512 tokens at the Mixtral-8x7B shape, every expert resident: T=1024 "
+                                    "d_model=4096 d_ff=14336 E=8 top-2 SwiGLU, bf16")
+
     # ---------------- the oracle on the host cores, on a bounded sample of the prefill workload ------------
     if not args.no_cpu_baseline:
         import numpy as np

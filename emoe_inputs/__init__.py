@@ -91,7 +91,9 @@ X1 = LayerConfig("X1_mixtral_8x22b_prefill_bf16", 5, 4096, 6144, 16384, 8, 2, 4,
 X2 = LayerConfig("X2_openmoe_like_bf16", 6, 2048, 2048, 8192, 32, 2, 16, BF16, SWIGLU, zipf_s=1.1)
 # one short prompt at the Mixtral-8x7B shape (a few dozen rows per expert: between a decode step and a batch of prompts)
 X3 = LayerConfig("X3_mixtral_one_prompt_bf16", 7, 256, 4096, 14336, 8, 2, 6, BF16, SWIGLU)
-EXTRA_CONFIGS = {"X1": X1, "X2": X2, "X3": X3}
+# two prompts of 512 tokens with every expert resident (the first prompt of Section 3.3): about 256 rows per slot
+X4 = LayerConfig("X4_mixtral_two_prompts_bf16", 8, 1024, 4096, 14336, 8, 2, 8, BF16, SWIGLU)
+EXTRA_CONFIGS = {"X1": X1, "X2": X2, "X3": X3, "X4": X4}
 
 
 def small_variant(cfg: LayerConfig, *, T: Optional[int] = None, d_model: Optional[int] = None,

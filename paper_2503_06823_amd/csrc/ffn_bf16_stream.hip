@@ -30,12 +30,15 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
 // weight rows per workgroup: template parameter WR, 64 (two MFMA row blocks) or 32 (one; plain and
-// ReLU passes only, used when 64-row units would give fewer workgroups than the chip can hold)
+// ReLU passes only, used when 64-row units would give fewer workgroups than the chip can hold).
+// A 32-row unit's stage is half token rows, so it gets five stages instead of three (80 KiB, still
+// two workgroups per CU): 64 KiB of weights in flight per CU like the 64-row units, where three
+// workgroups of three stages hold 48 (second product of the Mixtral decode step: 126 -> 120 us).
 constexpr int TOK = 32;                     // token rows per pass
 constexpr int BK = 128;                     // K elements per tile
 constexpr int ROW_BYTES = BK * 2;           // 256
 constexpr int X_BYTES = TOK * ROW_BYTES;    // 8 KiB
-constexpr int STAGES = 3;
+constexpr int kMinStages = 3;               // LDS stages of one K tile each: 3 at 64 weight rows, 5 at 32
 constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per tile row
 constexpr int RPI = 1024 / ROW_BYTES;       // tile rows filled by one load instruction
 constexpr int SPW = BK / 16 / 4;            // MFMA steps per wavefront and tile
@@ -44,7 +47,7 @@ constexpr int LX = X_BYTES / 1024 / 4;      // token load instructions per wavef
 constexpr int kStreamOnce = 2;
 constexpr unsigned kRotation = 21;           // K-tile rotation per workgroup (measured best of 1..29)
 constexpr int RED_BYTES = 3 * 32 * 64 * 4;  // partial sums of wavefronts 1..3
-static_assert(RED_BYTES <= STAGES * (32 * ROW_BYTES + X_BYTES), "the reduction reuses the tile stages");
+static_assert(RED_BYTES <= kMinStages * (32 * ROW_BYTES + X_BYTES), "the reduction reuses the tile stages");
 
 // s_waitcnt immediate: vmcnt <= n and all LDS traffic done (vmcnt[3:0] | [15:14], expcnt [6:4], lgkmcnt [11:8])
 constexpr int wait_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0x0 << 8); }
@@ -62,7 +65,7 @@ __device__ __forceinline__ void barrier_keep_loads() {
 
 // grid.x = S * ceil(N / BNO) workgroups, BNO = output columns per workgroup (32 SwiGLU, else 64).
 template <int EPI, int WR, bool KTAIL>
-__global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
+__global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
                                                            const int32_t* __restrict__ offsets,
                                                            const bf16_t* __restrict__ b0,
                                                            const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
@@ -74,6 +77,7 @@ __global__ __launch_bounds__(256, WR == 64 ? 2 : 3) void stream_gemm_bf16(const 
     constexpr int LOADS = LW + LX;
     constexpr int NBLK = WR / 32;                    // MFMA row blocks
     static_assert(WR == 64 || (WR == 32 && EPI != kSwiglu), "unsupported unit shape");
+    constexpr int STAGES = WR == 64 ? 3 : 5;
     __shared__ __align__(16) char lds[STAGES * STAGE_BYTES];
     const int slot = blockIdx.x / n_units;
     const int n0 = (blockIdx.x % n_units) * BNO;

@@ -19,6 +19,10 @@
 // Three stages: while tile t is multiplied, tiles t+1 and t+2 are on their way, 64 KiB of weights
 // in flight per CU, which is what it takes to keep HBM busy at its latency.  The narrow token tile
 // is what buys the third stage: with 256 token rows only two and a half stages fit.
+// Up to 48 rows per slot on average the token tile is 64 rows (one row of four wavefronts, each 64
+// tokens x 64 weight rows): a stage is 8 + 32 KiB, four stages fit, 96 KiB of weights in flight,
+// and the weight panel of a slot of one m-tile is loaded with the non-temporal hint (first
+// product at the Mixtral shape, 8 slots of 22-38 rows: 345 -> 310 us, 6.1 TB/s).
 // The 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), chosen by which global
 // chunk a lane fetches, so the MFMA fragment reads (32 rows x one chunk) have no bank conflicts.
 // Chunks past K (when K is not a multiple of 64), rows past the slot's end and weight rows past N
@@ -56,13 +60,11 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int BM = 128;                    // token rows per tile
+constexpr int kTileRows = 128;             // token rows per tile (64 in the variant for slots of few rows)
 constexpr int BK = 64;                     // K elements per tile
 constexpr int ROW_BYTES = BK * 2;          // 128
-constexpr int X_TILE = BM * ROW_BYTES;     // 16 KiB
 constexpr int NW = 4;                      // wavefronts: 2 (tokens) x 2 (weight rows)
 constexpr int TB = 2;                      // 32-token blocks per wavefront
-constexpr int LX = BM / 8 / NW;            // token load instructions per wavefront and K tile (4)
 constexpr int XCDS = 8;
 constexpr int kCUs = 256;
 constexpr unsigned kRotation = 21;          // K-tile rotation per slot (best of 5, 21, 37 and an even spread)
@@ -85,6 +87,7 @@ __device__ __forceinline__ void barrier_keep_loads() {
 constexpr int kGroups = 256;  // the persistent launch: one workgroup per CU
 constexpr int kMinShare = 8;     // K tiles per workgroup, at least, when tiles are cut
 constexpr int kMinSpared = 48;   // tiles are cut only if that shortens every workgroup's K walk by this many K tiles
+constexpr long long kRowsPerSlot64 = 48;  // up to that many rows per slot on average: token tiles of 64 rows
 constexpr int kMinPersistK = 64; // K tiles from which on the persistent launch (which may cut) is used at all
 
 // The tiles of a launch and how a persistent launch shares them out, derived from slot_offsets by
@@ -96,11 +99,12 @@ struct Work {
     long long units;                      // tiles * kt: the sequence that is cut into shares
     int sharers;                          // > 0: tiles are cut, that many workgroups take equal shares; 0: whole tiles
 };
-__device__ __forceinline__ Work make_work(const int32_t* __restrict__ offsets, int S, int n_tiles, int K, int lane, int G) {
+__device__ __forceinline__ Work make_work(const int32_t* __restrict__ offsets, int S, int n_tiles, int K, int lane, int G,
+                                          int bm) {
     Work w;
     w.s_begin = lane < S ? offsets[lane] : 0;
     w.s_end = lane < S ? offsets[lane + 1] : 0;
-    w.s_mtiles = (w.s_end - w.s_begin + BM - 1) / BM;
+    w.s_mtiles = (w.s_end - w.s_begin + bm - 1) / bm;
     const int span = w.s_mtiles * n_tiles;
     int incl = span;
 #pragma unroll
@@ -130,15 +134,15 @@ __device__ __forceinline__ int share_of(const Work& w, long long u) {
     return (int)(((u + 1) * w.sharers + w.units - 1) / w.units) - 1;
 }
 // tile number -> slot, first row, end of the slot's rows, n-tile
-__device__ __forceinline__ void decode_tile(const Work& w, int S, int lane, int L, int& slot, int& row0, int& row_end,
-                                            int& nt) {
+__device__ __forceinline__ void decode_tile(const Work& w, int S, int lane, int L, int bm, int& slot, int& row0,
+                                            int& row_end, int& nt, int& mtiles) {
     // an empty slot starts where its successor does: the last slot that starts at or before L holds it
     slot = __popcll(__ballot(lane < S && w.first <= L)) - 1;
     const int rem = L - __builtin_amdgcn_readlane(w.first, slot);
-    const int mtiles = __builtin_amdgcn_readlane(w.s_mtiles, slot);
+    mtiles = __builtin_amdgcn_readlane(w.s_mtiles, slot);
     const int mt = rem % mtiles;
     nt = rem / mtiles;
-    row0 = __builtin_amdgcn_readlane(w.s_begin, slot) + mt * BM;
+    row0 = __builtin_amdgcn_readlane(w.s_begin, slot) + mt * bm;
     row_end = __builtin_amdgcn_readlane(w.s_end, slot);
 }
 // where a piece's accumulators go: workgroup g leaves at most two pieces, the end of the tile its
@@ -149,15 +153,21 @@ __device__ __forceinline__ int piece_slot(int g, bool starts_inside) { return 2 
 // STAGES: LDS stages of one K tile each (token rows + weight rows), STAGES - 1 of them in flight.
 // PERSIST: one workgroup per CU that takes whole tiles or, when they are few, an equal share of all
 // tiles' K tiles; otherwise one workgroup per tile and surplus workgroups exit.
-template <int EPI, int BR, int STAGES, bool KTAIL, bool PERSIST>
+template <int EPI, int BM, int BR, int STAGES, bool KTAIL, bool PERSIST>
 __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restrict__ a, RowGather gather,
                                                      const int32_t* __restrict__ offsets,
                                                      const bf16_t* __restrict__ b0, const bf16_t* __restrict__ b1,
                                                      bf16_t* __restrict__ c, float* __restrict__ partials, int S, int N,
                                                      int K, int n_tiles) {
     constexpr int W_TILE = BR * ROW_BYTES;             // 32 or 16 KiB
+    constexpr int X_TILE = BM * ROW_BYTES;             // 16 or 8 KiB
     constexpr int STAGE_BYTES = X_TILE + W_TILE;
-    constexpr int WB = BR / 2 / 32;                    // 32-row weight blocks per wavefront (4 or 2)
+    constexpr int WM = BM / 64, WN = NW / WM;          // wavefronts along the tokens (64 each) and along the weight rows
+    constexpr int LX = BM / 8 / NW;                    // token load instructions per wavefront and K tile (4 or 2)
+    constexpr int WB = BR / WN / 32;                   // 32-row weight blocks per wavefront (4 or 2)
+    static_assert(BM == 128 || BM == 64, "two or one wavefront rows of 64 tokens");
+    static_assert(!PERSIST || BM == kTileRows, "the second kernel adds pieces of 128-row tiles");
+    static_assert(EPI != kSwiglu || WB % 2 == 0, "a wavefront holds gate and up blocks of the same columns");
     constexpr int LW = BR / 8 / NW;                    // weight load instructions per wavefront and K tile
     constexpr int LPT = LX + LW;                       // loads per wavefront and K tile
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
@@ -169,10 +179,10 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     const int G = gridDim.x;
-    const Work work = make_work(offsets, S, n_tiles, K, lane, G);
+    const Work work = make_work(offsets, S, n_tiles, K, lane, G, BM);
     // workgroup ids go round-robin over the XCDs: g numbers them XCD by XCD
     const int xcd = blockIdx.x % XCDS, idx = blockIdx.x / XCDS;
     const int g = xcd * (G / XCDS) + idx;
@@ -219,8 +229,8 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
         int rr;
-        if (EPI == kSwiglu) rr = (i < WB / 2) ? wn * (BR / 4) + i * 32 : BR / 2 + wn * (BR / 4) + (i - WB / 2) * 32;
-        else rr = wn * (BR / 2) + i * 32;
+        if (EPI == kSwiglu) rr = (i < WB / 2) ? wn * (BR / 2 / WN) + i * 32 : BR / 2 + wn * (BR / 2 / WN) + (i - WB / 2) * 32;
+        else rr = wn * (BR / WN) + i * 32;
         w_off[i] = X_TILE + (rr + f_row) * ROW_BYTES + f_sw;
     }
 
@@ -240,8 +250,8 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
             cnt = (long long)(work.kt - kb) < u_end - u ? work.kt - kb : (int)(u_end - u);
             u += cnt;
         }
-        int slot, row0, row_end, nt;
-        decode_tile(work, S, lane, tile, slot, row0, row_end, nt);
+        int slot, row0, row_end, nt, slot_mtiles;
+        decode_tile(work, S, lane, tile, BM, slot, row0, row_end, nt, slot_mtiles);
         const int n0 = nt * BNO;
 
         uint32_t x_voff[LX], w_voff[LW];
@@ -272,7 +282,9 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
         // and the weight panel common to its m-tiles are fetched once.  A start per n-tile as well costs up
         // to 15 % once the slot's token rows no longer stay in L2 beside the weight stream.
         const int k_rot = (int)(((unsigned)slot * kRotation) % (unsigned)cnt);
-        auto issue_tile = [&](int st, int tk) {
+        // once: the weight panel of a slot of one m-tile is read by nobody else, and is loaded with the non-temporal hint
+        auto issue_tile = [&](int st, int tk, auto once_tag) {
+            constexpr int kWeightAux = decltype(once_tag)::value ? 2 : 0;
             int kk = tk + k_rot;
             kk = kk >= cnt ? kk - cnt : kk;
             int k0 = k_first + kk * BK;
@@ -289,7 +301,7 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                 uint32_t v = w_voff[i];
                 if ((KTAIL && k0 + w_chunk[i] * 8 >= K) || tk >= cnt) v = b_bytes;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    b_rsrc, (lds_void*)(lds + st * STAGE_BYTES + X_TILE + (LW * wave + i) * 1024), 16, (int)v, k0 * 2, 0, 0);
+                    b_rsrc, (lds_void*)(lds + st * STAGE_BYTES + X_TILE + (LW * wave + i) * 1024), 16, (int)v, k0 * 2, 0, kWeightAux);
             }
         };
 
@@ -329,20 +341,19 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
             }
         };
 
-        // ---- prologue: the trip's K tiles 0 .. STAGES-1 on their way, tile 0 landed ----------------------
-        // (every wavefront is past the last barrier of the previous trip: nobody reads LDS any more)
-#pragma unroll
-        for (int p = 0; p < STAGES; ++p) issue_tile(p, p);
-        barrier_keep_loads<(STAGES - 1) * LPT>();
-
         // ---- main loop -------------------------------------------------------------------------------------
         // Per K tile four MFMA steps of 16.  The barrier comes before the last step: by then every wavefront
         // holds its last fragments of tile t in registers, so the stage of tile t is free for the data of
         // tile t+STAGES, and tile t+1 has landed once only the loads of tiles t+2 .. t+STAGES-1 are pending.
         // The last step's MFMAs then cover the first fragment reads of tile t+1.
         // A wavefront whose 64 token rows all lie past the slot's end takes part in loads and barriers only.
-        auto k_loop = [&](auto idle_tag) {
+        auto k_loop = [&](auto idle_tag, auto once_tag) {
             constexpr bool IDLE = decltype(idle_tag)::value;
+            // prologue: the trip's K tiles 0 .. STAGES-1 on their way, tile 0 landed (every wavefront is past
+            // the last barrier of the previous trip: nobody reads LDS any more)
+#pragma unroll
+            for (int p = 0; p < STAGES; ++p) issue_tile(p, p, once_tag);
+            barrier_keep_loads<(STAGES - 1) * LPT>();
             if (!IDLE) load_frags(0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             int st = 0;
@@ -365,7 +376,7 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                 barrier_keep_loads<(STAGES - 2) * LPT>();
                 __builtin_amdgcn_sched_barrier(0);
                 if (!IDLE) load_frags(0, st1, 0);
-                issue_tile(st, t + STAGES);
+                issue_tile(st, t + STAGES, once_tag);
                 if (!IDLE) {
                     mfma_step(1);
                     interleave(std::true_type{});
@@ -374,8 +385,15 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                 st = st1;
             }
         };
-        if (row0 + wm * 64 >= row_end) k_loop(std::true_type{});
-        else k_loop(std::false_type{});
+        if constexpr (BM == 64) {
+            // With 96 KiB of weights in flight the hint is worth 6-10 % (it was a wash with the 64 KiB of the
+            // 128-row tiles); only where no other m-tile reads the panel.  One row of wavefronts: none is idle.
+            if (slot_mtiles == 1) k_loop(std::false_type{}, std::true_type{});
+            else k_loop(std::false_type{}, std::false_type{});
+        } else {
+            if (row0 + wm * 64 >= row_end) k_loop(std::true_type{}, std::false_type{});
+            else k_loop(std::false_type{}, std::false_type{});
+        }
         // the surplus loads must have landed (as zeros) before the stages are written again
         barrier_keep_loads<0>();
 
@@ -418,8 +436,8 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                             if (EPI == kRelu) t = fmaxf(t, 0.0f);
                             v[q] = t;
                         }
-                        // columns wn*(BNO/2) + ni*32 + 8 gq + 4*(lane/32) .. +3: chunk j, its lower or upper half
-                        const int j = wn * (BNO / 16) + ni * 4 + gq;
+                        // columns wn*(BNO/WN) + ni*32 + 8 gq + 4*(lane/32) .. +3: chunk j, its lower or upper half
+                        const int j = wn * (BNO / WN / 8) + ni * 4 + gq;
                         *reinterpret_cast<bf16x4*>(lds + r * ROWB + ((j ^ (r & SWM)) * 16) + (lane >> 5) * 8) =
                             __builtin_convertvector(v, bf16x4);
                     }
@@ -431,8 +449,8 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
         const int jc = lane % CPR;
         const int n = n0 + jc * 8;
 #pragma unroll 4
-        for (int it = 0; it < 32 / RPS; ++it) {
-            const int r = wave * 32 + it * RPS + lane / CPR;
+        for (int it = 0; it < BM / NW / RPS; ++it) {
+            const int r = wave * (BM / NW) + it * RPS + lane / CPR;
             const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & SWM)) * 16));
             if (row0 + r < row_end && n < N) *reinterpret_cast<uint4*>(c + (size_t)(row0 + r) * N + n) = val;
         }
@@ -456,7 +474,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int b = blockIdx.x + 1;
-    const Work work = make_work(offsets, S, n_tiles, K, lane, G);
+    const Work work = make_work(offsets, S, n_tiles, K, lane, G, kTileRows);
     if (b >= work.sharers) return;              // nothing was cut, or no share starts here
     const long long ub = share_begin(work, b);  // first unit of share b
     if (ub % work.kt == 0) return;              // the boundary falls between two tiles
@@ -464,8 +482,8 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
     const long long t_begin = (long long)tile * work.kt, t_end = t_begin + work.kt;
     const int g_first = share_of(work, t_begin), g_last = share_of(work, t_end - 1);
     if (g_first != b - 1) return;  // several boundaries inside one tile: the first of them does the work
-    int slot, row0, row_end, nt;
-    decode_tile(work, S, lane, tile, slot, row0, row_end, nt);
+    int slot, row0, row_end, nt, slot_mtiles;
+    decode_tile(work, S, lane, tile, kTileRows, slot, row0, row_end, nt, slot_mtiles);
     for (int unit = 0; unit < UNITS; ++unit) {
         const int mi = unit / NB, ni = unit % NB;
         if (row0 + wm * 64 + mi * 32 >= row_end) continue;  // this wavefront's block holds no rows: nothing was written
@@ -474,7 +492,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
         for (int v = 0; v < 16; ++v) { gate[v] = 0.0f; up[v] = 0.0f; }
         for (int gg = g_first; gg <= g_last; ++gg) {
             // share g_first holds the start of the tile (its piece starts at K tile 0), the others start inside it
-            const float* src = partials + (size_t)piece_slot(gg, gg != g_first) * (BM * BR) + tid;
+            const float* src = partials + (size_t)piece_slot(gg, gg != g_first) * (kTileRows * BR) + tid;
             float ga[16], ua[16];  // all loads of a piece in flight together, then the adds
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -510,15 +528,15 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
     }
 }
 
-template <int EPI, int BR, int STAGES, bool KTAIL, bool PERSIST>
+template <int EPI, int BM, int BR, int STAGES, bool KTAIL, bool PERSIST>
 hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
                       bf16_t* c, float* partials, long long m_tiles, int S, int N, int K, hipStream_t st) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
-    constexpr int kLds = STAGES * (X_TILE + BR * ROW_BYTES);
+    constexpr int kLds = STAGES * (BM * ROW_BYTES + BR * ROW_BYTES);
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     static_assert(!PERSIST || (size_t)2 * kGroups * BM * BR * sizeof(float) <= kMidPartialBytes,
                   "two pieces per workgroup fit the workspace");
-    auto kern = mid_gemm_bf16<EPI, BR, STAGES, KTAIL, PERSIST>;
+    auto kern = mid_gemm_bf16<EPI, BM, BR, STAGES, KTAIL, PERSIST>;
     static std::atomic<bool> attr_set{false};  // set once per kernel; setting it twice from two threads is harmless
     if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -538,19 +556,19 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
     return hipGetLastError();
 }
 
-template <int EPI, int BR, int STAGES, bool PERSIST>
+template <int EPI, int BM, int BR, int STAGES, bool PERSIST>
 hipError_t launch_ktail(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
                         bf16_t* c, float* partials, long long m_tiles, int S, int N, int K, hipStream_t st) {
     if (K % BK == 0)
-        return launch_cfg<EPI, BR, STAGES, false, PERSIST>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
-    return launch_cfg<EPI, BR, STAGES, true, PERSIST>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
+        return launch_cfg<EPI, BM, BR, STAGES, false, PERSIST>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
+    return launch_cfg<EPI, BM, BR, STAGES, true, PERSIST>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
 }
 
 template <int EPI>
 hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
                       bf16_t* c, float* partials, long long A, int S, int N, int K, hipStream_t st) {
-    // every slot adds at most one partial m-tile to the A / BM whole ones
-    const long long m_tiles = A / BM + (S < A ? S : A);
+    // every slot adds at most one partial m-tile to the A / 128 whole ones
+    const long long m_tiles = A / kTileRows + (S < A ? S : A);
     // Tiles of 256 weight rows, unless they would leave CUs without a tile (the second product of a
     // layer with a small d_model): then 128 weight rows and five stages, so that twice as many CUs
     // stream weights, each with as many bytes in flight; and if K is long, in a persistent launch
@@ -559,10 +577,14 @@ hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets,
     constexpr int BNO = EPI == kSwiglu ? 128 : 256;
     if (m_tiles * ((N + BNO - 1) / BNO) <= kCUs) {
         if ((K + BK - 1) / BK >= kMinPersistK)
-            return launch_ktail<EPI, 128, 5, true>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
-        return launch_ktail<EPI, 128, 5, false>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
+            return launch_ktail<EPI, 128, 128, 5, true>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
+        return launch_ktail<EPI, 128, 128, 5, false>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
     }
-    return launch_ktail<EPI, 256, 3, false>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
+    // Few rows per slot: token tiles of 64 rows leave LDS for a fourth stage, 96 KiB of weights in flight
+    // per CU instead of 64.
+    if (A <= kRowsPerSlot64 * S)
+        return launch_ktail<EPI, 64, 256, 4, false>(a, gather, offsets, b0, b1, c, partials, A / 64 + (S < A ? S : A), S, N, K, st);
+    return launch_ktail<EPI, 128, 256, 3, false>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
 }
 
 }  // namespace

@@ -35,6 +35,9 @@ SMALL_CASES = [
     cfg("mid_relu_wide_ff", act="relu", T=1500, d_model=72, d_ff=2560, E=64, k=1, R=16, zipf_s=1.1, index=66),
     cfg("mid_swiglu_wide_ff", T=800, d_model=72, d_ff=1408, E=16, k=2, R=16, index=67),
     cfg("mid_few_rows_per_slot", T=100, d_model=192, d_ff=264, E=8, k=2, R=5, index=60),
+    # 29-48 rows per slot and more tiles than CUs: token tiles of 64 rows (K tail, N tail, slots of 0 to 3 tiles)
+    cfg("mid_64_row_tiles_swiglu", T=320, d_model=72, d_ff=1792, E=16, k=2, R=16, index=72),
+    cfg("mid_64_row_tiles_relu", act="relu", T=640, d_model=136, d_ff=3336, E=64, k=1, R=16, zipf_s=1.1, index=73),
     # a long K and fewer 128 x 128 tiles than CUs: the persistent launch cuts the tiles along K and a second kernel
     # adds the pieces (first product: K = 4104 with a K tail; second product: K = 4160)
     cfg("mid_cut_first_product", T=100, d_model=4104, d_ff=264, E=8, k=2, R=3, index=68),

@@ -22,7 +22,9 @@
 // Up to 48 rows per slot on average the token tile is 64 rows (one row of four wavefronts, each 64
 // tokens x 64 weight rows): a stage is 8 + 32 KiB, four stages fit, 96 KiB of weights in flight,
 // and the weight panel of a slot of one m-tile is loaded with the non-temporal hint (first
-// product at the Mixtral shape, 8 slots of 22-38 rows: 345 -> 310 us, 6.1 TB/s).
+// product at the Mixtral shape, 8 slots of 22-38 rows: 345 -> 310 us, 6.1 TB/s).  With 128 weight
+// rows (plain and ReLU products) the 64-row arrangement has six stages of 8 + 16 KiB, 80 KiB of
+// weights in flight (second product at the same shape: 171 -> 149 us, 6.3 TB/s).
 // The 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), chosen by which global
 // chunk a lane fetches, so the MFMA fragment reads (32 rows x one chunk) have no bank conflicts.
 // Chunks past K (when K is not a multiple of 64), rows past the slot's end and weight rows past N
@@ -166,7 +168,6 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
     constexpr int LX = BM / 8 / NW;                    // token load instructions per wavefront and K tile (4 or 2)
     constexpr int WB = BR / WN / 32;                   // 32-row weight blocks per wavefront (4 or 2)
     static_assert(BM == 128 || BM == 64, "two or one wavefront rows of 64 tokens");
-    static_assert(!PERSIST || BM == kTileRows, "the second kernel adds pieces of 128-row tiles");
     static_assert(EPI != kSwiglu || WB % 2 == 0, "a wavefront holds gate and up blocks of the same columns");
     constexpr int LW = BR / 8 / NW;                    // weight load instructions per wavefront and K tile
     constexpr int LPT = LX + LW;                       // loads per wavefront and K tile
@@ -463,18 +464,19 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
 // which walks the 32 x 32 block positions of a wavefront's accumulators.
 // Workgroup b - 1: boundary b = 1 .. G-1 lies between shares b-1 and b.  When the main kernel
 // took whole tiles, which the host cannot know, every workgroup exits after reading slot_offsets.
-template <int EPI, int BR>
+template <int EPI, int BM, int BR>
 __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
                                                  const float* __restrict__ partials, int S, int N, int K,
                                                  int n_tiles, int G) {
-    constexpr int WB = BR / 2 / 32;
+    constexpr int WM = BM / 64, WN = NW / WM;  // as in the main kernel
+    constexpr int WB = BR / WN / 32;
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
     constexpr int UNITS = TB * NB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int b = blockIdx.x + 1;
-    const Work work = make_work(offsets, S, n_tiles, K, lane, G, kTileRows);
+    const Work work = make_work(offsets, S, n_tiles, K, lane, G, BM);
     if (b >= work.sharers) return;              // nothing was cut, or no share starts here
     const long long ub = share_begin(work, b);  // first unit of share b
     if (ub % work.kt == 0) return;              // the boundary falls between two tiles
@@ -483,7 +485,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
     const int g_first = share_of(work, t_begin), g_last = share_of(work, t_end - 1);
     if (g_first != b - 1) return;  // several boundaries inside one tile: the first of them does the work
     int slot, row0, row_end, nt, slot_mtiles;
-    decode_tile(work, S, lane, tile, kTileRows, slot, row0, row_end, nt, slot_mtiles);
+    decode_tile(work, S, lane, tile, BM, slot, row0, row_end, nt, slot_mtiles);
     for (int unit = 0; unit < UNITS; ++unit) {
         const int mi = unit / NB, ni = unit % NB;
         if (row0 + wm * 64 + mi * 32 >= row_end) continue;  // this wavefront's block holds no rows: nothing was written
@@ -492,7 +494,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
         for (int v = 0; v < 16; ++v) { gate[v] = 0.0f; up[v] = 0.0f; }
         for (int gg = g_first; gg <= g_last; ++gg) {
             // share g_first holds the start of the tile (its piece starts at K tile 0), the others start inside it
-            const float* src = partials + (size_t)piece_slot(gg, gg != g_first) * (kTileRows * BR) + tid;
+            const float* src = partials + (size_t)piece_slot(gg, gg != g_first) * (BM * BR) + tid;
             float ga[16], ua[16];  // all loads of a piece in flight together, then the adds
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -510,7 +512,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
         const int r = row0 + wm * 64 + mi * 32 + (lane & 31);
         if (r >= row_end) continue;
         bf16_t* crow = c + (size_t)r * N;
-        const int col0 = nt * BNO + wn * (BNO / 2) + ni * 32 + (lane >> 5) * 4;
+        const int col0 = nt * BNO + wn * (BNO / WN) + ni * 32 + (lane >> 5) * 4;
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             const int n = col0 + 8 * gq;
@@ -547,7 +549,7 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
     const int n_tiles = (N + BNO - 1) / BNO;
     if (PERSIST) {
         kern<<<kGroups, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
-        mid_fixup<EPI, BR><<<kGroups - 1, 64 * NW, 0, st>>>(offsets, c, partials, S, N, K, n_tiles, kGroups);
+        mid_fixup<EPI, BM, BR><<<kGroups - 1, 64 * NW, 0, st>>>(offsets, c, partials, S, N, K, n_tiles, kGroups);
     } else {
         const long long tiles = m_tiles * n_tiles;
         const unsigned blocks = (unsigned)((tiles + XCDS - 1) / XCDS * XCDS);
@@ -575,15 +577,25 @@ hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets,
     // that cuts the tiles along K when even they are clearly fewer than the CUs (with a short K that
     // never pays, and the second kernel's launch is saved).
     constexpr int BNO = EPI == kSwiglu ? 128 : 256;
+    // Few rows per slot: token tiles of 64 rows leave LDS for more stages, 96 (80 with 128 weight rows) KiB
+    // of weights in flight per CU instead of 64.  (With SwiGLU and 128 weight rows a wavefront of the
+    // 64-row arrangement would hold half a block of gate rows: that combination keeps 128 token rows.)
+    const bool few_rows = A <= kRowsPerSlot64 * S;
+    const long long m_tiles64 = A / 64 + (S < A ? S : A);
+    const bool persist = (K + BK - 1) / BK >= kMinPersistK;
     if (m_tiles * ((N + BNO - 1) / BNO) <= kCUs) {
-        if ((K + BK - 1) / BK >= kMinPersistK)
+        if constexpr (EPI != kSwiglu) {
+            if (few_rows && persist)
+                return launch_ktail<EPI, 64, 128, 6, true>(a, gather, offsets, b0, b1, c, partials, m_tiles64, S, N, K, st);
+            if (few_rows)
+                return launch_ktail<EPI, 64, 128, 6, false>(a, gather, offsets, b0, b1, c, partials, m_tiles64, S, N, K, st);
+        }
+        if (persist)
             return launch_ktail<EPI, 128, 128, 5, true>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
         return launch_ktail<EPI, 128, 128, 5, false>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
     }
-    // Few rows per slot: token tiles of 64 rows leave LDS for a fourth stage, 96 KiB of weights in flight
-    // per CU instead of 64.
-    if (A <= kRowsPerSlot64 * S)
-        return launch_ktail<EPI, 64, 256, 4, false>(a, gather, offsets, b0, b1, c, partials, A / 64 + (S < A ? S : A), S, N, K, st);
+    if (few_rows)
+        return launch_ktail<EPI, 64, 256, 4, false>(a, gather, offsets, b0, b1, c, partials, m_tiles64, S, N, K, st);
     return launch_ktail<EPI, 128, 256, 3, false>(a, gather, offsets, b0, b1, c, partials, m_tiles, S, N, K, st);
 }
 

@@ -42,6 +42,9 @@ SMALL_CASES = [
     # adds the pieces (first product: K = 4104 with a K tail; second product: K = 4160)
     cfg("mid_cut_first_product", T=100, d_model=4104, d_ff=264, E=8, k=2, R=3, index=68),
     cfg("mid_cut_second_product", act="relu", T=240, d_model=200, d_ff=4160, E=8, k=1, R=4, index=69),
+    # the same with at most 48 rows per slot: 64-row token tiles in the persistent launch (plain and ReLU products)
+    cfg("mid_64_row_cut_second_product", T=80, d_model=200, d_ff=4160, E=8, k=2, R=4, index=74),
+    cfg("mid_64_row_cut_first_product_relu", act="relu", T=160, d_model=4104, d_ff=264, E=8, k=1, R=4, index=75),
     # a long K and about as many tiles as CUs, or more: the persistent launch takes whole tiles, one or two each
     cfg("mid_persistent_whole_tiles", T=300, d_model=4096, d_ff=1152, E=8, k=2, R=8, index=70),
     cfg("mid_persistent_two_rounds", act="relu", T=1600, d_model=4096, d_ff=2048, E=64, k=1, R=16, zipf_s=1.1, index=71),

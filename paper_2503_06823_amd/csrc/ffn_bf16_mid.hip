@@ -386,13 +386,16 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                 st = st1;
             }
         };
-        if constexpr (BM == 64) {
-            // With 96 KiB of weights in flight the hint is worth 6-10 % (it was a wash with the 64 KiB of the
-            // 128-row tiles); only where no other m-tile reads the panel.  One row of wavefronts: none is idle.
-            if (slot_mtiles == 1) k_loop(std::false_type{}, std::true_type{});
-            else k_loop(std::false_type{}, std::false_type{});
+        // The weight panel of a slot of one m-tile is read by nobody else: non-temporal hint, so that the stream
+        // does not push the token rows out of the caches (-5 to -12 % per product at 22-110 rows per slot; not
+        // for the pieces of a cut tile, where it cost 3 %).
+        const bool once = slot_mtiles == 1 && !cut;
+        const bool idle = row0 + wm * 64 >= row_end;  // never with one row of wavefronts
+        if (once) {
+            if (BM == 128 && idle) k_loop(std::true_type{}, std::true_type{});
+            else k_loop(std::false_type{}, std::true_type{});
         } else {
-            if (row0 + wm * 64 >= row_end) k_loop(std::true_type{}, std::false_type{});
+            if (BM == 128 && idle) k_loop(std::true_type{}, std::false_type{});
             else k_loop(std::false_type{}, std::false_type{});
         }
         // the surplus loads must have landed (as zeros) before the stages are written again

@@ -23,8 +23,8 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per launch of the dominant kernels, from two hardware-counter runs of this command
 # (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for a 1 GiB device copy:
 # x2.00 and x1.00).  Counters cannot be read from inside the process, so the figures are carried here.
-TRAFFIC_BYTES_PREFILL_PASS1 = (1535452.3 * 2.00 + 279769.0 * 1.00) * 1024   # 3.43 GB: operands re-read through L2
-TRAFFIC_BYTES_DECODE_PASS1 = (690266.2 * 2.00 + 3635.8 * 1.00) * 1024        # 1.417 GB: 1.006x the weight bytes
+TRAFFIC_BYTES_PREFILL_PASS1 = (1534893.4 * 2.00 + 278873.0 * 1.00) * 1024   # 3.43 GB: operands re-read through L2
+TRAFFIC_BYTES_DECODE_PASS1 = (690267.1 * 2.00 + 3627.3 * 1.00) * 1024        # 1.417 GB: 1.006x the weight bytes
 
 
 def log(msg):

@@ -366,6 +366,10 @@ def main():
                                     "X4 two prompts of 512 tokens at the Mixtral-8x7B shape, every expert resident: T=1024 "
                                     "d_model=4096 d_ff=14336 E=8 top-2 SwiGLU, bf16")
 
+        result["x5"] = other_config(torch, P, gen, gen.X5, 30, 5, 2,
+                                    "X5 decode step of 128 tokens at the Mixtral-8x7B shape, every expert resident: T=128 "
+                                    "d_model=4096 d_ff=14336 E=8 top-2 SwiGLU, bf16; 2 rotating copies of the slot buffers")
+
     # ---------------- the oracle on the host cores, on a bounded sample of the prefill workload ------------
     if not args.no_cpu_baseline:
         import numpy as np

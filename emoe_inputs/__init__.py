@@ -93,7 +93,10 @@ X2 = LayerConfig("X2_openmoe_like_bf16", 6, 2048, 2048, 8192, 32, 2, 16, BF16, S
 X3 = LayerConfig("X3_mixtral_one_prompt_bf16", 7, 256, 4096, 14336, 8, 2, 6, BF16, SWIGLU)
 # two prompts of 512 tokens with every expert resident (the first prompt of Section 3.3): about 256 rows per slot
 X4 = LayerConfig("X4_mixtral_two_prompts_bf16", 8, 1024, 4096, 14336, 8, 2, 8, BF16, SWIGLU)
-EXTRA_CONFIGS = {"X1": X1, "X2": X2, "X3": X3, "X4": X4}
+# a decode step of 128 tokens with every expert resident: 32 rows per slot on average, between the streaming
+# kernels' range and a prompt's
+X5 = LayerConfig("X5_mixtral_decode128_bf16", 9, 128, 4096, 14336, 8, 2, 8, BF16, SWIGLU)
+EXTRA_CONFIGS = {"X1": X1, "X2": X2, "X3": X3, "X4": X4, "X5": X5}
 
 
 def small_variant(cfg: LayerConfig, *, T: Optional[int] = None, d_model: Optional[int] = None,

@@ -11,10 +11,10 @@ from gpu_util import DeviceLayer, check_outputs, check_routing_and_permutation
 
 pytestmark = pytest.mark.gpu
 
-SAMPLE = {"C1": None, "C2": 256, "C3": 16, "C4": 16, "C5": 96, "X1": 8, "X2": 48, "X3": 16, "X4": 16}
+SAMPLE = {"C1": None, "C2": 256, "C3": 16, "C4": 16, "C5": 96, "X1": 8, "X2": 48, "X3": 16, "X4": 16, "X5": 16}
 
 
-@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5"])
 def test_full_size_workload(gpu_device, name):
     cfg = gen.CONFIGS.get(name) or gen.EXTRA_CONFIGS[name]
     print(f"full-size {cfg.name}: generating", flush=True)

@@ -64,7 +64,7 @@ const char *emoe_status_string(int status);
 
 /* Bytes of device workspace emoe_permute and emoe_expert_ffn need for `desc`
  * (either output pointer may be NULL).  Pure host arithmetic.  The FFN workspace is
- * h [A,f] in dtype plus, for bf16 layers with more than 28 rows per slot on average,
+ * h [A,f] in dtype plus, for bf16 layers with more than 22 rows per slot on average,
  * 32 or 64 MiB of fp32 partial sums of output tiles cut along K.  Neither workspace
  * needs initialising, and nothing in them outlives a call except h between the two
  * passes of emoe_expert_ffn_pass.  Calls that may run at the same time (different

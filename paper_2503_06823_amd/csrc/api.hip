@@ -51,14 +51,16 @@ FfnWs ffn_ws_layout(const emoe_layer_desc& d) {
 
 // Row counts live on the device, so the choice goes by the average number of rows per slot.
 // Few rows per slot: reading the weights dominates, use the streaming kernels.  They take 32 rows
-// of a slot per pass over its weights, so they win only while (nearly) every slot fits one pass:
-// at the Mixtral shape 369 us against the tiled kernels' 477 us with 21 rows per slot, but 661 us
-// against 477 us with 42; random routing at 28 rows per slot on average puts about one slot in
-// five over 32 rows.  Up to kMidRowsPerSlot rows per slot the tiles of 128 token rows are used:
-// their variant with 128 weight rows per tile runs the second product faster (Mixtral shape, 8
-// slots, whole FFN: 522 us against the large tiles' 538 us at 64 rows per slot, 539 against 552 us
-// at 96), but they lose once many slots need a second tile (128 rows per slot: 723 against 563 us).
-constexpr long long kStreamRowsPerSlot = 28;
+// of a slot per pass over its weights, so they win only while every slot fits one pass, and lose
+// a fifth as soon as one does not: at the Mixtral shape, 8 slots of 16-31 rows 454 us against the
+// 64-row tiles' 455 us, but 16-35 rows 535 against 450 us; 6 slots of 15-26 rows 357 against
+// 361 us, 18-35 rows 428 against 369 us.  With 22 rows per slot on average a slot of more than 32
+// is rare under even routing.  Up to kMidRowsPerSlot rows per slot the tiles of 128 (up to 48: 64)
+// token rows are used: they keep more weight bytes in flight than the tiles of 256 token rows
+// (Mixtral shape, 8 slots, whole FFN: 493 us against the large tiles' 538 us at 64 rows per slot,
+// 527 against 552 us at 96), but they lose once many slots need a second tile (128 rows per slot:
+// 723 against 563 us).
+constexpr long long kStreamRowsPerSlot = 22;
 constexpr long long kMidRowsPerSlot = 100;
 // A small layer (all resident slots' weights stream in some 60 us) is bound by how well its tiles
 // fill the chip, not by the weight stream, and around 256 rows per slot the 128-row tiles fill it

@@ -98,7 +98,7 @@ def test_workspace_sizes_scale_with_the_layer():
 
 
 def test_ffn_workspace_holds_the_partial_sums_of_the_tile_paths():
-    """The bf16 FFN takes one of three paths by the average rows per slot (A / S): up to 28 the
+    """The bf16 FFN takes one of three paths by the average rows per slot (A / S): up to 22 the
     streaming kernels (h only), up to 100 the 128-row tiles (h + 32 MiB of K pieces), above that
     the 256-row tiles (h + a 256-byte plan + 64 MiB); fp32 needs h only.  A layer whose weights are
     small is an exception to the last step."""
@@ -106,7 +106,7 @@ def test_ffn_workspace_holds_the_partial_sums_of_the_tile_paths():
         return (T * k * f * elem + 255) // 256 * 256
     S, k, f = 4, 2, 256
     # a small layer takes the 128-row tiles again from 170 to 300 rows per slot
-    for T, extra in ((56, 0), (57, 32 << 20), (200, 32 << 20), (201, 256 + (64 << 20)), (339, 256 + (64 << 20)),
+    for T, extra in ((44, 0), (45, 32 << 20), (200, 32 << 20), (201, 256 + (64 << 20)), (339, 256 + (64 << 20)),
                      (340, 32 << 20), (600, 32 << 20), (601, 256 + (64 << 20)), (4096, 256 + (64 << 20))):
         assert P.emoe_workspace_bytes(good(T=T, S=S, k=k, d_ff=f))[1] == h_bytes(T, k, f, 2) + extra, T
     assert P.emoe_workspace_bytes(good(T=4096, S=S, k=k, d_ff=f, dtype="f32"))[1] == h_bytes(4096, k, f, 4)

@@ -24,7 +24,7 @@ SMALL_CASES = [
     gen.C1,                                                                       # fp32 path, as specified
     cfg("f32_ragged", dtype="f32", T=150, d_model=72, d_ff=136, E=8, k=2, R=5, S=7, index=41),
     cfg("f32_relu_top1", dtype="f32", act="relu", T=97, d_model=64, d_ff=200, E=16, k=1, R=6, zipf_s=1.1, index=42),
-    # tiles of 128 token rows (28 S < A <= 100 S): slots of less than one tile and (the skewed ones) of
+    # tiles of 128 token rows (22 S < A <= 100 S): slots of less than one tile and (the skewed ones) of
     # several, N tails, K tail (d=328, f=456 not % 64), empty slots, top-6
     cfg("mid_swiglu_ragged", T=190, d_model=328, d_ff=456, E=8, k=2, R=4, index=43),
     cfg("mid_swiglu_aligned", T=240, d_model=512, d_ff=768, E=8, k=2, R=3, S=5, index=44),
@@ -55,10 +55,10 @@ SMALL_CASES = [
     # few output tiles and a long K: leftover tiles are split along K into pieces (with a K tail in both passes)
     cfg("tiled_splitk_ktail", T=800, d_model=1032, d_ff=1160, E=8, k=2, R=4, index=64),
     cfg("tiled_topk6", T=1600, d_model=256, d_ff=384, E=64, k=6, R=24, zipf_s=1.2, resident="popular", index=65),
-    # streaming path (A <= 28 S): few rows per slot, slots with 0 rows, a slot with > 64 rows
+    # streaming path (A <= 22 S): few rows per slot, slots with 0 rows, a slot with > 64 rows
     cfg("stream_decode", T=64, d_model=512, d_ff=1088, E=8, k=2, R=6, index=47),
     cfg("stream_ktail", T=20, d_model=200, d_ff=328, E=8, k=2, R=5, S=8, index=48),
-    cfg("stream_relu_hot_slot", act="relu", T=90, d_model=256, d_ff=384, E=4, k=1, R=2, S=4, zipf_s=3.0, index=49),
+    cfg("stream_relu_hot_slot", act="relu", T=88, d_model=256, d_ff=384, E=4, k=1, R=2, S=4, zipf_s=3.0, index=49),
     cfg("stream_two_token_blocks", T=80, d_model=128, d_ff=192, E=4, k=1, R=2, S=4, index=57),
     cfg("stream_k_equals_R", T=9, d_model=128, d_ff=192, E=6, k=3, R=3, index=50),
     # few tokens, few experts, long rows: the bf16 route that puts one workgroup on each token (d_model with a K tail)

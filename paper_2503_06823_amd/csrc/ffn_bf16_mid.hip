@@ -387,9 +387,8 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
             }
         };
         // The weight panel of a slot of one m-tile is read by nobody else: non-temporal hint, so that the stream
-        // does not push the token rows out of the caches (-5 to -12 % per product at 22-110 rows per slot; not
-        // for the pieces of a cut tile, where it cost 3 %).
-        const bool once = slot_mtiles == 1 && !cut;
+        // does not push the token rows out of the caches (-5 to -12 % per product at 22-110 rows per slot).
+        const bool once = slot_mtiles == 1;
         const bool idle = row0 + wm * 64 >= row_end;  // never with one row of wavefronts
         if (once) {
             if (BM == 128 && idle) k_loop(std::true_type{}, std::true_type{});

@@ -589,7 +589,10 @@ hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets,
         if constexpr (EPI != kSwiglu) {
             if (few_rows && persist)
                 return launch_ktail<EPI, 64, 128, 6, true>(a, gather, offsets, b0, b1, c, partials, m_tiles64, S, N, K, st);
-            if (few_rows)
+            // a short K (no cutting) and so few 128-row tiles that they leave a quarter of the CUs idle even
+            // if every slot has a partial tile: 64-row tiles, about twice as many
+            const bool underfilled = !persist && m_tiles * ((N + 127) / 128) <= kCUs * 3 / 4;
+            if (few_rows || underfilled)
                 return launch_ktail<EPI, 64, 128, 6, false>(a, gather, offsets, b0, b1, c, partials, m_tiles64, S, N, K, st);
         }
         if (persist)

@@ -403,16 +403,16 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // (w, i) fills tile rows (LPW*w + i)*8 .. +7, 128 bytes each.  Lane l lands in row l>>3, chunk
         // position l&7 and therefore fetches global chunk (l&7) ^ ((row>>1)&7).
         uint32_t a_voff[LPW], b_voff[LPW];
-        int chunk[LPW];
+        int chunk[LPW], a_row[LPW];
+        // the rows of x come through perm: those loads go out first, the first weight tile is requested
+        // while they are on their way (further down), and only then are the token addresses formed
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int tr = (LPW * wave + i) * RPI + l_row;  // row of the tile
             chunk[i] = l_pos ^ ((tr >> 1) & 7);
             int r = row0 + tr;
-            const bool past = r >= row_end;  // rows past the slot's end: out of range, zeros without memory traffic
-            r = past ? row_end - 1 : r;
-            if (gather.perm != nullptr) r = gather.perm[r] / gather.k;  // the token's row of x, not a copy of it
-            a_voff[i] = past ? a_bytes : ((uint32_t)r * (uint32_t)K + chunk[i] * 8) * 2u;
+            r = r >= row_end ? row_end - 1 : r;
+            a_row[i] = gather.perm != nullptr ? gather.perm[r] : r;  // the token's row of x (times k), not a copy of it
             int n = n0 + (EPI == kSwiglu ? tr % (BR / 2) : tr);  // SwiGLU: second half = same rows of W3
             n = n < N ? n : N - 1;
             b_voff[i] = ((uint32_t)n * (uint32_t)K + chunk[i] * 8) * 2u;
@@ -514,12 +514,20 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // (every wavefront is past the last barrier of the previous trip, so nobody reads LDS any more)
         // Ring slots: token rows of K tile t in slot 2t mod 5, weight rows in slot 2t+1 mod 5.
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int i = 0; i < LPW; ++i) issue_load(false, i, 1, 0);
 #pragma unroll
-            for (int i = 0; i < LPW; ++i) issue_load(true, i, 2 * t, t);
-#pragma unroll
-            for (int i = 0; i < LPW; ++i) issue_load(false, i, 2 * t + 1, t);
+        for (int i = 0; i < LPW; ++i) {
+            const int tr = (LPW * wave + i) * RPI + l_row;
+            const bool past = row0 + tr >= row_end;  // rows past the slot's end: out of range, zeros without memory traffic
+            const int r = gather.perm != nullptr ? a_row[i] / gather.k : a_row[i];
+            a_voff[i] = past ? a_bytes : ((uint32_t)r * (uint32_t)K + chunk[i] * 8) * 2u;
         }
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) issue_load(true, i, 0, 0);
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) issue_load(true, i, 2, 1);
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) issue_load(false, i, 3, 1);
         barrier_keep_loads<2 * LPW>();
 
         // ---- main loop -----------------------------------------------------------------------------

@@ -12,6 +12,15 @@ import paper_2503_06823_amd as P
 # tolerances of the parity contract
 TOL_WEIGHT = 1e-5
 TOL_OUT = {"bf16": 1e-2, "f32": 1e-5}
+# Element-wise bounds |got - ref| <= REL * |ref| + ABS * rms(ref row).
+# bf16: a value is rounded once to 8 significant bits, at most 2^-8 of itself (2^-7 if the fp32 value sat next
+# to a rounding boundary on the other side of it than the exact value).  h: that rounding plus the fp32
+# accumulation error of the two products (2^-12 of the row's rms is a generous cover).  y_perm and out: the
+# rounding of y plus the roundings of the f values of h carried through the second product, a sum of f
+# independent errors whose standard deviation is about 2^-9.3 of the row's rms; 2^-6 is ten of them.
+# fp32: accumulation error only.
+TOL_ELEM = {"bf16": {"h": (2.0 ** -7, 2.0 ** -12), "y": (2.0 ** -7, 2.0 ** -6)},
+            "f32": {"h": (1e-5, 1e-5), "y": (1e-5, 1e-5)}}
 
 
 def to_dev(a, dtype: str, device="cuda:0"):
@@ -62,7 +71,7 @@ class DeviceLayer:
     def check_gather_path_is_identical(self):
         """The FFN that reads token rows through perm must reproduce y_perm and out bit for bit."""
         b = self.buf
-        y0, o0, h0 = b.y_perm.clone(), b.out.clone(), b.ffn_ws.clone()
+        y0, o0 = b.y_perm.clone(), b.out.clone()
         b.y_perm.fill_(0); b.out.fill_(0); b.x_perm.fill_(0)
         self.forward(gather_in_ffn=True)
         torch.cuda.synchronize()
@@ -105,4 +114,70 @@ def check_outputs(dl: DeviceLayer, ref: oracle.LayerResult):
     # worst single token, reported (looser bound: one token has fewer terms to average over)
     per_tok = np.linalg.norm(out - ref.out, axis=1) / np.maximum(np.linalg.norm(ref.out, axis=1), 1e-30)
     assert per_tok.max() <= 4 * tol, f"worst token rel-L2 {per_tok.max():.3e}"
+    rel, abs_rms = TOL_ELEM[cfg.dtype]["y"]
+    check_elementwise(to_f64(b.y_perm)[rows], y_ref, rel, abs_rms, "y_perm")
+    # out: the bounds of its k rows of y carried through the combine, plus its own rounding
+    bound = rel * np.abs(ref.out)
+    for j in range(cfg.k):
+        yj = np.stack([ref.y_rows[int(r)] for r in ref.permutation.inv_perm[ref.tokens.astype(np.int64) * cfg.k + j]])
+        wj = ref.topk_weight[ref.tokens, j][:, None]
+        bound += wj * (rel * np.abs(yj) + abs_rms * np.sqrt((yj * yj).mean(axis=1, keepdims=True)))
+    excess = np.abs(out - ref.out) - bound
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0, f"out: element {worst} got {out[worst]!r} ref {ref.out[worst]!r}"
     return err
+
+
+def check_elementwise(got: np.ndarray, ref: np.ndarray, rel: float, abs_rms: float, what: str):
+    """|got - ref| <= rel * |ref| + abs_rms * rms(ref row), for every element."""
+    rms = np.sqrt((ref * ref).mean(axis=1, keepdims=True))
+    excess = np.abs(got - ref) - (rel * np.abs(ref) + abs_rms * rms)
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0, (f"{what}: element {worst} got {got[worst]!r} ref {ref[worst]!r}, "
+                                f"row rms {rms[worst[0], 0]:.4g}")
+
+
+def stratified_rows(slot_offsets: np.ndarray, seed: int, block: int = 32) -> np.ndarray:
+    """Grouped rows to compare at full size: of every slot its first and last row and one seeded row
+    of every `block`-row block counted from the slot's start.  Every kernel here cuts a slot's rows
+    into tiles at multiples of 32 rows from the slot's start and multiplies them in blocks of 32, so
+    this puts a row into every block of every m-tile; a row is compared over all its columns, which
+    covers every n-tile, whole or cut along K."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for s in range(len(slot_offsets) - 1):
+        b, e = int(slot_offsets[s]), int(slot_offsets[s + 1])
+        if e <= b:
+            continue
+        rows += [b, e - 1]
+        for lo in range(b, e, block):
+            rows.append(int(rng.integers(lo, min(lo + block, e))))
+    return np.unique(np.asarray(rows, dtype=np.int64))
+
+
+def h_rows(dl: DeviceLayer, rows: np.ndarray) -> np.ndarray:
+    """Rows of the intermediate h [A, f], which the FFN leaves at the start of its workspace."""
+    cfg = dl.cfg
+    A, f = cfg.T * cfg.k, cfg.d_ff
+    el = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    h = dl.buf.ffn_ws[:A * f * cfg.elem_bytes].view(el).view(A, f)
+    return to_f64(h[torch.from_numpy(rows).to(h.device)])
+
+
+def check_ffn_rows(dl: DeviceLayer, pm: oracle.Permutation, rows: np.ndarray):
+    """h and y_perm of the given grouped rows against the oracle's FFN of the same (token, slot)
+    pairs: relative L2 over the block and the element-wise bound.  Returns both relative errors."""
+    cfg, inp = dl.cfg, dl.inp
+    row_token = (pm.perm[rows] // cfg.k).astype(np.int32)
+    row_slot = (np.searchsorted(pm.slot_offsets, rows, side="right") - 1).astype(np.int32)
+    y_ref, h_ref = oracle.expert_ffn_rows(row_token, row_slot, inp.x, inp.w1_slots, inp.w3_slots, inp.w2_slots,
+                                          cfg.act, cfg.dtype, return_h=True)
+    tol, el = TOL_OUT[cfg.dtype], TOL_ELEM[cfg.dtype]
+    h_got = h_rows(dl, rows)
+    y_got = to_f64(dl.buf.y_perm[torch.from_numpy(rows).to(dl.buf.y_perm.device)])
+    h_err, y_err = rel_l2(h_got, h_ref), rel_l2(y_got, y_ref)
+    assert h_err <= tol, f"h rel-L2 {h_err:.3e} > {tol}"
+    assert y_err <= tol, f"y_perm rel-L2 {y_err:.3e} > {tol}"
+    check_elementwise(h_got, h_ref, *el["h"], "h")
+    check_elementwise(y_got, y_ref, *el["y"], "y_perm")
+    return h_err, y_err

@@ -1,17 +1,22 @@
 """GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
-Routing and the permutation are compared in full (bit-exact); the FFN and the combine on a seeded
-sample of tokens that the oracle computes one by one."""
+Routing and the permutation are compared in full (bit-exact).  The expert FFN is compared on a
+stratified sample of grouped rows that the oracle computes one by one: of every slot the first and the
+last row and a seeded row of every 32-row block, so that every output tile of every round of the
+persistent launch, every tile cut along K and every ragged last tile holds compared rows; both the
+intermediate h and y_perm, by relative L2 and element by element.  The combine is compared on a seeded
+sample of tokens."""
 import numpy as np
 import pytest
 import torch
 
 import emoe_inputs as gen
 import oracle
-from gpu_util import DeviceLayer, check_outputs, check_routing_and_permutation
+from gpu_util import DeviceLayer, check_ffn_rows, check_outputs, check_routing_and_permutation, stratified_rows
 
 pytestmark = pytest.mark.gpu
 
-SAMPLE = {"C1": None, "C2": 256, "C3": 16, "C4": 16, "C5": 96, "X1": 8, "X2": 48, "X3": 16, "X4": 16, "X5": 16}
+# tokens whose `out` the oracle computes (each costs k FFN rows); None = all
+TOKEN_SAMPLE = {"C1": None, "C2": 256, "C3": 16, "C4": None, "C5": 96, "X1": 8, "X2": 48, "X3": 16, "X4": 16, "X5": 16}
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5"])
@@ -19,7 +24,7 @@ def test_full_size_workload(gpu_device, name):
     cfg = gen.CONFIGS.get(name) or gen.EXTRA_CONFIGS[name]
     print(f"full-size {cfg.name}: generating", flush=True)
     inp = gen.make_layer_inputs(cfg)
-    n = SAMPLE[name]
+    n = TOKEN_SAMPLE[name]
     tokens = None if n is None else np.sort(np.random.default_rng(cfg.seed).choice(cfg.T, n, replace=False))
     print(f"full-size {cfg.name}: oracle on {n or cfg.T} tokens", flush=True)
     ref = oracle.layer_forward(inp, tokens=tokens)
@@ -31,6 +36,10 @@ def test_full_size_workload(gpu_device, name):
     err = check_outputs(dl, ref)
     counts = ref.permutation.slot_counts
     print(f"full-size {cfg.name}: out rel-L2 {err:.3e}; rows per slot min {counts.min()} max {counts.max()}", flush=True)
+    rows = stratified_rows(ref.permutation.slot_offsets, cfg.seed)
+    print(f"full-size {cfg.name}: oracle FFN on {rows.size} stratified rows of {cfg.T * cfg.k}", flush=True)
+    h_err, y_err = check_ffn_rows(dl, ref.permutation, rows)
+    print(f"full-size {cfg.name}: h rel-L2 {h_err:.3e}, y_perm rel-L2 {y_err:.3e}", flush=True)
     # properties that hold for every token, not only the sample
     out = dl.buf.out.float()
     assert torch.isfinite(out).all()

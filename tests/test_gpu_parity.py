@@ -8,7 +8,8 @@ import torch
 import emoe_inputs as gen
 import oracle
 import paper_2503_06823_amd as P
-from gpu_util import DeviceLayer, check_outputs, check_routing_and_permutation, desc_of, to_dev
+from gpu_util import (DeviceLayer, check_ffn_rows, check_outputs, check_routing_and_permutation, desc_of,
+                      stratified_rows, to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -80,6 +81,11 @@ def test_layer_matches_oracle(gpu_device, c, shuffle):
     torch.cuda.synchronize()
     check_routing_and_permutation(dl, ref)
     check_outputs(dl, ref)
+    # the intermediate h as well, element by element (all rows of a small case)
+    A = c.T * c.k
+    if A > 0:
+        rows = np.arange(A) if A <= 4096 else stratified_rows(ref.permutation.slot_offsets, c.seed)
+        check_ffn_rows(dl, ref.permutation, rows)
     dl.check_gather_path_is_identical()
 
 

@@ -121,6 +121,22 @@ int emoe_permute(const emoe_layer_desc *desc, const void *x, const int32_t *topk
                  int32_t *inv_perm, void *x_perm, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * emoe_permute for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same inputs, outputs, result and errors as emoe_permute, without `ws`: the
+ * per-workgroup slot counts live in a 256 KiB array that the library keeps in every GPU's
+ * memory from the moment it is loaded until the process ends.  The call allocates and frees
+ * nothing.  Limit: ceil(T*k / 1024) * S <= 65536, else EMOE_ERR_WORKSPACE (nothing is
+ * enqueued).  All calls on one GPU share that GPU's array: calls that may overlap on one
+ * GPU (different streams, or threads) race; calls on one stream, one after the other, do
+ * not, and nothing needs clearing between them.  The first call on a device looks the
+ * array's address up (a host-side query, no stream work); make it outside graph capture.
+ */
+int emoe_permute_static(const emoe_layer_desc *desc, const void *x, const int32_t *topk_expert,
+                        const int32_t *slot_of_expert, int32_t *slot_counts, int32_t *slot_offsets, int32_t *perm,
+                        int32_t *inv_perm, void *x_perm, void *stream);
+
+/*
  * Expert FFN over the grouped rows, only for slots that received rows ("fewer
  * experts ... reduce the compute latency and global GPU memory read operations",
  * Section 5.1).  For slot s and rows r in [slot_offsets[s], slot_offsets[s+1]):

@@ -23,6 +23,7 @@ DTYPES = {"f32": EMOE_F32, "bf16": EMOE_BF16}
 ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
 
 EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_route_observe", "emoe_permute",
+           "emoe_permute_static",
            "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_combine",
            "emoe_layer_forward", "emoe_load_experts", "emoe_expected_tokens",
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
@@ -61,6 +62,7 @@ def lib() -> ctypes.CDLL:
         L.emoe_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.emoe_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.emoe_permute.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.emoe_permute_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.emoe_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_expert_ffn_pass.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
@@ -143,6 +145,14 @@ def emoe_permute(desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets
                             _ptr(slot_offsets), _ptr(perm), _ptr(inv_perm), _ptr(x_perm), _ptr(ws), int(ws_bytes),
                             _stream(stream))
     return _check(rc, "emoe_permute", check)
+
+
+def emoe_permute_static(desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm, x_perm,
+                        stream=None, check=True) -> int:
+    rc = lib().emoe_permute_static(ctypes.byref(desc), _ptr(x), _ptr(topk_expert), _ptr(slot_of_expert),
+                                   _ptr(slot_counts), _ptr(slot_offsets), _ptr(perm), _ptr(inv_perm), _ptr(x_perm),
+                                   _stream(stream))
+    return _check(rc, "emoe_permute_static", check)
 
 
 def emoe_expert_ffn(desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes, stream=None,

@@ -11,10 +11,42 @@
 //                 when the caller wants indices only)
 // An assignment whose expert is not resident (only possible when the caller broke emoe_route's
 // precondition) is left out: inv_perm = -1, and it appears in no slot.
+#include <mutex>
+
 #include "common.h"
 
 namespace emoe {
 namespace {
+
+// Scratch of emoe_permute_static, the variant of emoe_permute for callers that cannot allocate: the
+// per-workgroup slot counts live in this array instead of a caller workspace.  Every GPU the library
+// runs on holds its own copy at its own address until the process ends.  In host code the array's
+// name is only a stand-in for the symbol; its address on the current device comes from
+// hipGetSymbolAddress (static_scratch() below) and that pointer is what kernels receive.
+constexpr size_t kStaticScratchInts = 65536;  // int32 [ceil(A / 1024)][S]
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+int32_t* scratch_of_device[kMaxDevices] = {};
+
+// The current device's copy of `scratch`, looked up once per device.
+hipError_t static_scratch(int32_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_of_device[dev] == nullptr) {
+        int32_t* ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        scratch_of_device[dev] = ptr;
+    }
+    *out = scratch_of_device[dev];
+    return hipSuccess;
+}
 
 constexpr int kThreads = 256;
 constexpr int kPasses = kPermuteChunk / kThreads;
@@ -246,3 +278,29 @@ hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t
 }
 
 }  // namespace emoe
+
+extern "C" int emoe_permute_static(const emoe_layer_desc* desc, const void* x, const int32_t* topk_expert,
+                                   const int32_t* slot_of_expert, int32_t* slot_counts, int32_t* slot_offsets,
+                                   int32_t* perm, int32_t* inv_perm, void* x_perm, void* stream) {
+    using namespace emoe;
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!topk_expert || !slot_of_expert || !slot_counts || !slot_offsets || !perm || !inv_perm) return EMOE_ERR_NULL;
+    if (x_perm && !x) return EMOE_ERR_NULL;
+    const long long A = (long long)desc->T * desc->k;
+    const long long n_blocks = (A + kPermuteChunk - 1) / kPermuteChunk;
+    if (n_blocks * desc->S > (long long)kStaticScratchInts) return EMOE_ERR_WORKSPACE;  // beyond the static scratch
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (desc->T == 0) {
+        hipError_t z1 = launch_fill_i32(slot_counts, desc->S, 0, st);
+        hipError_t z2 = launch_fill_i32(slot_offsets, desc->S + 1, 0, st);
+        return (z1 == hipSuccess && z2 == hipSuccess) ? EMOE_OK : EMOE_ERR_DEVICE;
+    }
+    int32_t* ptr = nullptr;
+    if (static_scratch(&ptr) != hipSuccess) return EMOE_ERR_DEVICE;
+    // Nothing in the scratch has to start at zero: the count kernel writes every entry that the scan
+    // and place kernels read, so what the previous call left there is overwritten before it is read.
+    hipError_t e = launch_permute(*desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm, x_perm,
+                                  ptr, st);
+    return e == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}

@@ -1,8 +1,9 @@
 /*
  * emoe.h -- C ABI of the resident-expert MoE layer for AMD MI355X (gfx950).
  *
- * One MoE layer forward ("a gate and a collection of experts", eMoE Section 1)
- * computed over only those experts that are currently resident in GPU memory.
+ * One MoE layer forward (a gating function that scores the experts and a set of
+ * expert networks of which each token uses a few, eMoE Section 1) computed over
+ * only those experts that are currently resident in GPU memory.
  * The rule that makes this the paper's layer and not the ordinary one is in
  * Section 3.2.2 (last paragraph): a token whose chosen expert is not on the
  * GPU is routed to its next-best expert that is.
@@ -54,10 +55,15 @@ typedef struct {
     int32_t d_ff;    /* f                                           */
     int32_t E;       /* experts the gate scores                     */
     int32_t k;       /* experts per token                           */
-    int32_t S;       /* expert slots in GPU memory                  */
+    int32_t S;       /* expert slots in GPU memory (see note below) */
     int32_t dtype;   /* emoe_dtype of x, weights, x_perm, y_perm, out */
     int32_t act;     /* emoe_act                                    */
 } emoe_layer_desc;
+
+/* Note on S: the row counts of the slots live on the device, so the expert FFN picks its kernels
+ * (weight streaming, small or large tiles) on the host from T*k / S, the average rows per slot if
+ * every slot is occupied.  Results do not depend on it, speed does: size S to the resident budget
+ * (the L of Section 3.4), not to E, when far fewer experts are resident than exist. */
 
 /* Static description of a status code; never NULL, never freed. */
 const char *emoe_status_string(int status);
@@ -74,7 +80,7 @@ int emoe_workspace_bytes(const emoe_layer_desc *desc, size_t *permute_ws_bytes, 
 /*
  * Gate and resident-restricted top-k (Section 1: the gate; Section 3.2.2: fallback
  * to the next-best resident expert; Section 3.2.2 first paragraphs: the routing
- * result is "a series of k indices" per token).
+ * result of a token is a list of k expert indices).
  *   logit[t,e] = sum_i x[t,i] * w_gate[e,i] (+ gate_bias[e]), fp32 accumulation.
  *   Among experts with slot_of_expert[e] >= 0, the k largest logits in descending
  *   order (ties: lower expert index) -> topk_expert[t,0..k-1] (expert ids).
@@ -90,9 +96,9 @@ int emoe_route(const emoe_layer_desc *desc, const void *x, const void *w_gate, c
                const int32_t *slot_of_expert, int32_t *topk_expert, float *topk_weight, void *stream);
 
 /*
- * emoe_route that also observes the experts' workload (Section 3.2.2: experts
- * are loaded "prioritizing those with the higher workload", the number of tokens
- * an expert receives).  Outputs as emoe_route; in addition, for every token,
+ * emoe_route that also observes the experts' workload (Section 3.2.2: when memory
+ * is short the experts with the larger workload are loaded first, the workload
+ * being the number of tokens an expert receives).  Outputs as emoe_route; in addition, for every token,
  * expert_tokens[e] += 1 for each of the k experts the token would use if every
  * expert were resident (the k largest logits over all E experts, same tie rule).
  * expert_tokens [E] int64 dev, in/out: counts accumulate across calls (a layer
@@ -137,9 +143,9 @@ int emoe_permute_static(const emoe_layer_desc *desc, const void *x, const int32_
                         int32_t *inv_perm, void *x_perm, void *stream);
 
 /*
- * Expert FFN over the grouped rows, only for slots that received rows ("fewer
- * experts ... reduce the compute latency and global GPU memory read operations",
- * Section 5.1).  For slot s and rows r in [slot_offsets[s], slot_offsets[s+1]):
+ * Expert FFN over the grouped rows, only for slots that received rows (Section 5.1
+ * attributes the method's latency gain to exactly this: with fewer experts there
+ * is less to compute and less to read from GPU memory).  For slot s and rows r in [slot_offsets[s], slot_offsets[s+1]):
  *   SwiGLU: h = silu(x_perm[r] W1_s^T) * (x_perm[r] W3_s^T),  y_perm[r] = h W2_s^T
  *   ReLU  : h = max(x_perm[r] W1_s^T, 0),                      y_perm[r] = h W2_s^T
  * Products accumulate in fp32; h and y_perm are rounded once to dtype.
@@ -186,7 +192,7 @@ int emoe_combine(const emoe_layer_desc *desc, const void *y_perm, const int32_t 
                  const float *topk_weight, void *out, void *stream);
 
 /*
- * The whole layer (Section 1: a gate and a collection of experts, here over the resident
+ * The whole layer (Section 1: gate plus experts, here over the resident
  * experts only, Section 3.2.2): emoe_route, emoe_permute (indices only), emoe_expert_ffn_gather
  * and emoe_combine enqueued in this order on `stream`, with the same arguments, results and
  * errors as the four calls; nothing else is done and nothing is allocated.  All the intermediate
@@ -226,9 +232,14 @@ int emoe_layer_forward(const emoe_layer_desc *desc, const void *x, const void *w
  * reads these slots") -> copies in list order -> both device maps rewritten ->
  * record done_event (if not NULL).  A forward that must see the new experts
  * waits on done_event first.
- * Errors (nothing enqueued, mirror untouched): EMOE_ERR_RESIDENT for ids out of
- * range, a slot named twice, an expert named twice, or a resulting map with fewer
- * than k resident experts.
+ * Errors found by validation (nothing enqueued, mirror untouched): EMOE_ERR_RESIDENT
+ * for ids out of range, a slot named twice, an expert named twice, or a resulting
+ * map with fewer than k resident experts; EMOE_ERR_NULL / _SHAPE as everywhere.
+ * EMOE_ERR_DEVICE (a HIP call failed while enqueueing) is different: copies
+ * issued before the failure stay enqueued, the device maps and done_event may
+ * not have been written and the mirror is left as it was, so the named slots
+ * and both device maps are undefined until the next successful call that names
+ * the same slots; the caller should treat those slots as empty.
  */
 int emoe_load_experts(const emoe_layer_desc *desc, int32_t n, const int32_t *expert_ids, const int32_t *slot_ids,
                       const void *const *host_w1, const void *const *host_w3, const void *const *host_w2,
@@ -296,7 +307,12 @@ int emoe_plan_load(int32_t E, int32_t S, int32_t k, const int32_t *expert_of_slo
  *                 workload order.  Plans every layer (emoe_plan_load) and then
  *                 enqueues the changed layers' loads on the side stream in
  *                 layer order; each waits until that layer's last forward has
- *                 released its slots.  On an error nothing has been enqueued.
+ *                 released its slots.  All layers are planned and validated
+ *                 before the first is enqueued, so an argument error enqueues
+ *                 nothing and changes nothing.  EMOE_ERR_DEVICE from layer i
+ *                 leaves layers before i loaded and recorded in their mirrors
+ *                 (they are consistent and usable), layer i as described for
+ *                 emoe_load_experts, and later layers untouched.
  *   layer_begin   call before layer i's forward: makes compute_stream wait for
  *                 the layer's pending load, if any (no stale weights).
  *   layer_end     call after layer i's forward: marks on compute_stream the

@@ -9,7 +9,7 @@
  *
  * What the paper fixes (Section 3.2.2, last paragraph): when the expert chosen
  * for a token is not resident, the token goes to its next-best expert that is.
- * The layer itself is the usual "gate + experts" block (Section 1) of the
+ * The layer itself is the usual gate-plus-experts block (Section 1) of the
  * models the paper serves (Section 2.1).  Readings taken where the paper is
  * silent:
  *   - every token always gets exactly k resident experts (absent ones are

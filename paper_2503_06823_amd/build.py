@@ -31,8 +31,8 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra, obj_dir: str = OBJ) -> str:
+    obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 target feature and says so: harmless
@@ -42,6 +42,14 @@ def _compile(src: str, extra) -> str:
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj
+
+
+def compile_objects(obj_dir: str, extra_flags=(), jobs: int = 8):
+    """Compile every HIP source into `obj_dir` with extra flags (e.g. host-side sanitizers for the
+    host-code checks in tests/test_sanitize.py); returns the object paths.  libemoe.so is not touched."""
+    os.makedirs(obj_dir, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        return list(ex.map(lambda s: _compile(s, list(extra_flags), obj_dir), SOURCES))
 
 
 def build_library(force: bool = True, jobs: int = 8, extra_flags=()) -> str:

@@ -20,11 +20,49 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
-# HBM bytes per launch of the dominant kernels, from two hardware-counter runs of this command
-# (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for a 1 GiB device copy:
-# x2.00 and x1.00).  Counters cannot be read from inside the process, so the figures are carried here.
-TRAFFIC_BYTES_PREFILL_PASS1 = (1534893.4 * 2.00 + 278873.0 * 1.00) * 1024   # 3.43 GB: operands re-read through L2
-TRAFFIC_BYTES_DECODE_PASS1 = (690267.1 * 2.00 + 3627.3 * 1.00) * 1024        # 1.417 GB: 1.006x the weight bytes
+# HBM bytes per launch of the dominant kernels come from two hardware-counter runs of this command
+# (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for a 1 GiB device copy).
+# Counters cannot be read from inside the process: `python -m paper_2503_06823_amd.profile_tools traffic`
+# turns the two runs into this tracked summary, whose machine-readable block is read back here.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "ffn_hbm_traffic_c3_prefill_c4_decode.md")
+
+
+def measured_traffic(kernel_prefix):
+    """HBM bytes per launch (fetched + written, scaled) of the kernel whose name starts with
+    `kernel_prefix`, from the tracked counter summary; None if the summary does not hold it."""
+    try:
+        text = open(TRAFFIC_SUMMARY).read()
+        block = text.split("```json", 1)[1].split("```", 1)[0]
+        for k in json.loads(block)["kernels"]:
+            if k["kernel"].startswith(kernel_prefix):
+                return k["hbm_bytes_per_launch"]
+    except (OSError, IndexError, KeyError, ValueError):
+        pass
+    return None
+
+
+def host_cpu():
+    """CPU model name and the number of physical cores of the machine, from /proc/cpuinfo."""
+    model, cores = "unknown", set()
+    try:
+        phys = core = None
+        for line in open("/proc/cpuinfo"):
+            key, _, val = line.partition(":")
+            key, val = key.strip(), val.strip()
+            if key == "model name":
+                model = val
+            elif key == "physical id":
+                phys = val
+            elif key == "core id":
+                core = val
+            elif not key and phys is not None:
+                cores.add((phys, core))
+                phys = core = None
+        if phys is not None:
+            cores.add((phys, core))
+    except OSError:
+        pass
+    return model, len(cores) or None
 
 
 def log(msg):
@@ -63,6 +101,11 @@ def timed_steps(torch, P, dev, buf, steps, warmup, weight_sets):
     wall = time.perf_counter() - t0
     names = ["route_permute", "ffn_pass1", "ffn_pass2", "combine"]
     ms = {n: sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j, n in enumerate(names)}
+    for j, n in enumerate(names):     # median and minimum over the timed steps, per call
+        v = sorted(e[j].elapsed_time(e[j + 1]) for e in ev)
+        ms[n + "_median"], ms[n + "_min"] = v[len(v) // 2], v[0]
+    v = sorted(e[0].elapsed_time(e[4]) for e in ev)
+    ms["step_median"], ms["step_min"] = v[len(v) // 2], v[0]
     return wall, ms
 
 
@@ -114,6 +157,60 @@ def graph_steps(torch, P, dev, buf, steps, warmup, weight_sets):
     return time.perf_counter() - t0
 
 
+def miss_rate(torch, P, dev, buf):
+    """Fraction of the (token, rank) pairs whose expert under ordinary top-k routing is not resident, so
+    that the fallback rule of Section 3.2.2 reroutes the token: the layer's routing is run once more
+    with every expert marked resident and its choices are looked up in the real slot map (all on the
+    device, from the library's results)."""
+    d = buf.desc
+    everyone = torch.arange(d.E, dtype=torch.int32, device=dev.x.device)
+    free = torch.empty_like(buf.topk_expert)
+    w = torch.empty_like(buf.topk_weight)
+    P.emoe_route(d, dev.x, dev.w_gate, dev.gate_bias, everyone, free, w)
+    torch.cuda.synchronize()
+    return float((dev.slot_of_expert[free.long()] < 0).float().mean())
+
+
+def measure_ceilings(torch, P, x, w, read_buffers):
+    """What this GPU sustains on the two resources that bound the FFN, with kernels that do nothing else:
+    the matrix-instruction loop on the workload's own operand values (no global traffic) and a plain
+    read stream over weight buffers (rotated so no launch finds its data cached)."""
+    res = {}
+    sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    iters = 896     # 256 workgroups x 896 rounds = 1.924 TFLOP, one launch of the prefill layer's first product
+    for key, lds in (("mfma_loop_with_lds_reads", True), ("mfma_loop_registers_only", False)):
+        for _ in range(3):
+            P.emoe_measure_mfma_loop(x, w, lds, 256, iters, sink)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(21)]
+        ev[0].record()
+        for i in range(20):
+            flop = P.emoe_measure_mfma_loop(x, w, lds, 256, iters, sink)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(20))
+        res[key] = {"tflops_mean": flop / (sum(t) / 20 * 1e-3) / 1e12, "tflops_best": flop / (t[0] * 1e-3) / 1e12,
+                    "launch_ms_mean": sum(t) / 20, "launches": 20, "flop_per_launch": flop}
+    sink16 = torch.empty(4, dtype=torch.int32, device="cuda")
+    best = None
+    for wgs in (2048, 4096, 8192, 16384):
+        nbytes = [b.numel() * b.element_size() // 32768 * 32768 for b in read_buffers]
+        for i in range(len(read_buffers)):
+            P.emoe_measure_read_stream(read_buffers[i], nbytes[i], wgs, sink16)
+        n = 12
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record()
+        for i in range(n):
+            P.emoe_measure_read_stream(read_buffers[i % len(read_buffers)], nbytes[i % len(read_buffers)], wgs, sink16)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        gbs = sum(nbytes[i % len(read_buffers)] for i in range(n)) / (ev[0].elapsed_time(ev[n]) * 1e-3) / 1e9
+        if best is None or gbs > best["gbs"]:
+            best = {"gbs": gbs, "workgroups": wgs, "bytes_per_launch": nbytes[0], "launches": n}
+    res["read_stream"] = best
+    log(f"ceilings: {res}")
+    return res
+
+
 def layer_work(cfg, counts):
     """Algorithmic work of one layer forward: flop of the routed rows, weight bytes of the non-empty slots."""
     A = cfg.T * cfg.k
@@ -122,15 +219,21 @@ def layer_work(cfg, counts):
     return 2.0 * A * mats * cfg.d_model * cfg.d_ff, occupied * mats * cfg.d_model * cfg.d_ff * cfg.elem_bytes
 
 
-def other_config(torch, P, gen, cfg, steps, warmup, copies, label):
-    _, wall, ms, counts, dev, buf = run_workload(torch, P, gen, cfg, steps, warmup, copies)
+def other_config(torch, P, gen, cfg, steps, warmup, copies, label, graph=False):
+    _, wall, ms, counts, dev, buf = run_workload(torch, P, gen, cfg, steps, warmup, copies, graph=graph)
+    missed = miss_rate(torch, P, dev, buf)
     del dev, buf
     torch.cuda.empty_cache()
     flop, wbytes = layer_work(cfg, counts)
+    extra = {}
+    if graph:       # a launch-bound layer is timed as a replayed HIP graph, like the decode step
+        extra = {"launch": "one HIP graph per weight copy, replayed", "ms_per_step_eager": wall / steps * 1e3}
+        wall = ms.pop("graph_wall_s")
     t = wall / steps
-    log(f"{cfg.name}: {t * 1e3:.3f} ms/step, breakdown {ms}")
+    log(f"{cfg.name}: {t * 1e3:.3f} ms/step, miss rate {missed:.3f}, breakdown {ms}")
     return {"config": {"workload": label, "rows_per_slot_max": int(counts.max()), "slots_with_rows": int((counts > 0).sum())},
             "value": cfg.T / t, "unit": "tokens/s", "ms_per_step": t * 1e3, "steps": steps, "breakdown_ms": ms,
+            "miss_rate": missed, **extra,
             "layer_tflops": flop / t / 1e12, "layer_mfma_frac": flop / t / 1e12 / PEAK_BF16_MFMA_TFLOPS,
             "layer_weight_gbs": wbytes / t / 1e9, "layer_hbm_frac": wbytes / t / 1e9 / PEAK_HBM_GBS}
 
@@ -251,12 +354,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the matrix-loop and read-stream ceiling measurements")
     ap.add_argument("--no-extras", action="store_true", help="skip the upload measurement and the C5 / C2 workloads")
     ap.add_argument("--more-shapes", action="store_true",
                     help="also time a Mixtral-8x22B-shaped prefill layer, an OpenMoE-shaped layer and one short prompt at the Mixtral-8x7B shape")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = size the sample for about 15 s")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="first run a plain 1 GiB device-to-device copy, so that a hardware-counter run of this "
+                    help="first run the library's plain copy kernel on 1 GiB, so that a hardware-counter run of this "
                          "command also holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -276,7 +380,7 @@ def main():
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read, 1 GiB written per copy
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            P.emoe_measure_copy_stream(src, dst, 1 << 30, 8192)
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
@@ -299,7 +403,7 @@ def main():
                                "4 of 8 experts resident, bf16", "rows_per_slot": [int(c) for c in counts]},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16<SwiGLU> + splitk_fixup (FFN pass 1)", "achieved": tf1,
                      "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": tf1 / PEAK_BF16_MFMA_TFLOPS,
-                     "traffic": TRAFFIC_BYTES_PREFILL_PASS1, "traffic_unit": "bytes per launch",
+                     "traffic": measured_traffic("grouped_gemm_bf16<1"), "traffic_unit": "bytes per launch",
                      "launch_ms": ms["ffn_pass1"]},
         "prefill_breakdown_ms": ms,
         "prefill_layer_mfma_frac": (flop_pass1 + flop_pass2) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
@@ -307,6 +411,17 @@ def main():
     }
     log(f"prefill: {ms_step:.3f} ms/step, {tokens_s:,.0f} tokens/s, pass1 {tf1:.0f} TFLOP/s, breakdown {ms}")
 
+    result["prefill_miss_rate"] = miss_rate(torch, P, dev3, buf3)
+    ceilings = None
+    if not args.no_ceilings:
+        # measured ceilings beside the datasheet peaks: the matrix-instruction loop on this layer's own token rows
+        # and weights, a read stream over its three weight buffers (470 MB each, rotated)
+        ceilings = measure_ceilings(torch, P, dev3.x, dev3.w1_slots, [dev3.w1_slots, dev3.w3_slots, dev3.w2_slots])
+        result["ceilings"] = ceilings
+        ach = ceilings["mfma_loop_with_lds_reads"]["tflops_mean"]
+        result["roofline"].update({"achievable": ach, "frac_of_achievable": tf1 / ach,
+                                   "achievable_kernel": "matrix-instruction loop with the GEMM's LDS fragment reads on this "
+                                                        "layer's operand values, no global traffic, same flop per launch"})
     if not args.no_extras:
         result["load_experts"] = bench_load(torch, P, gen, c3, dev3, buf3)
     del inp3, dev3, buf3
@@ -318,6 +433,7 @@ def main():
         dsteps, dwarm = max(args.steps, 30), max(args.warmup, 6)
         _, dwall_eager, dms, dcounts, ddev, dbuf = run_workload(torch, P, gen, c4, dsteps, dwarm, copies=3, graph=True)
         dwall = dms.pop("graph_wall_s")     # the step as a replayed HIP graph; the eager run gives the per-call times
+        dmiss = miss_rate(torch, P, ddev, dbuf)
         del ddev, dbuf
         torch.cuda.empty_cache()
         el = c4.elem_bytes
@@ -333,12 +449,16 @@ def main():
                                    "bf16; 3 rotating copies of the slot buffers", "rows_per_slot": [int(c) for c in dcounts]},
             "roofline": {"bound": "hbm", "kernel": "stream_gemm_bf16<SwiGLU> (FFN pass 1)", "achieved": gbs1,
                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs1 / PEAK_HBM_GBS,
-                         "traffic": TRAFFIC_BYTES_DECODE_PASS1, "traffic_unit": "bytes per launch",
+                         "traffic": measured_traffic("stream_gemm_bf16<1"), "traffic_unit": "bytes per launch",
                          "algorithmic_bytes": bytes_pass1, "launch_ms": dms["ffn_pass1"]},
-            "breakdown_ms": dms,
+            "breakdown_ms": dms, "miss_rate": dmiss,
             "pass2_gbs": bytes_pass2 / (dms["ffn_pass2"] * 1e-3) / 1e9,
             "layer_hbm_frac": (bytes_pass1 + bytes_pass2) / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         }
+        if ceilings:
+            ach = ceilings["read_stream"]["gbs"]
+            result["decode"]["roofline"].update({"achievable": ach, "frac_of_achievable": gbs1 / ach,
+                                                 "achievable_kernel": "plain read stream over 470 MB weight buffers"})
         log(f"decode: {d_ms:.3f} ms/step as a graph ({dwall_eager / dsteps * 1e3:.3f} eager), pass1 {gbs1:.0f} GB/s, breakdown {dms}")
 
     # ---------------- the other workloads (reported, not the headline) ----------------
@@ -348,7 +468,7 @@ def main():
                                     "resident (the most popular), Zipf(1.2) gate bias, bf16")
         result["c2"] = other_config(torch, P, gen, gen.C2, 40, 8, 4,
                                     "C2 Switch-style layer: T=1024 d_model=768 d_ff=3072 E=64 top-1 ReLU, 16 of 64 resident, "
-                                    "Zipf(1.1) gate bias, bf16; 4 rotating copies of the slot buffers")
+                                    "Zipf(1.1) gate bias, bf16; 4 rotating copies of the slot buffers", graph=True)
 
     if args.more_shapes:
         result["x1"] = other_config(torch, P, gen, gen.X1, 10, 3, 1,
@@ -389,11 +509,28 @@ def main():
         t = time.perf_counter()
         oracle.layer_forward(inp, tokens=toks)
         cpu_s = time.perf_counter() - t
+        model, physical = host_cpu()
         result["cpu_baseline"] = {
             "value": n / cpu_s, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{n} of the {c3.T} prefill tokens through the fp64 oracle (routing and permutation of all "
-                      f"tokens, FFN and combine of the sample), {cpu_s:.1f} s"}
+                      f"tokens, FFN and combine of the sample), {cpu_s:.1f} s",
+            "cpu_model": model, "physical_cores_of_the_machine": physical,
+            "threads_note": "cores = OpenMP threads the oracle ran on (the share of the machine this process may use)"}
         log(f"cpu baseline: {n} tokens in {cpu_s:.1f}s on {oracle.num_threads()} threads")
+        del inp
+        # the small workloads whole, best of three (decode step and Switch-style layer)
+        others = {}
+        for key, cfg in (("c4_decode", gen.C4), ("c2_switch", gen.C2)):
+            cin = gen.make_layer_inputs(cfg)
+            ts = []
+            for _ in range(3):
+                t = time.perf_counter()
+                oracle.layer_forward(cin)
+                ts.append(time.perf_counter() - t)
+            others[key] = {"value": cfg.T / min(ts), "unit": "tokens/s", "best_of": 3, "seconds": sorted(ts),
+                           "sample": f"all {cfg.T} tokens"}
+        result["cpu_baseline"]["other_workloads"] = others
+        log(f"cpu baseline, small workloads whole: {others}")
 
     print(json.dumps(result), flush=True)
 

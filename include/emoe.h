@@ -384,6 +384,30 @@ int emoe_schedule(int32_t n_waiting, const emoe_request *waiting, int32_t n_sche
                   const emoe_request *scheduled, int64_t t_max, double c, int32_t *admitted, int32_t *n_admitted);
 int emoe_generation_tick(emoe_request *request, int32_t completed, double reset_fraction);
 
+/*
+ * Measurement aids (no step of the layer; for the benchmark's measured ceilings beside the
+ * datasheet peaks).  Both only enqueue one kernel on `stream`; the caller times it.
+ *
+ * emoe_measure_mfma_loop: `workgroups` workgroups of four wavefronts each copy a 256 x 64 tile
+ * of a and of b (dev, bf16, a_elems / b_elems elements, at least 16384 each; pass the workload's
+ * own token rows and weights so that the operand values are the GEMM's) into LDS once and then
+ * issue `iters` rounds of 4 x 16 matrix instructions (v_mfma_f32_32x32x16_bf16, 4 x 4 blocks per
+ * wavefront as in the tiled FFN kernel) with no global memory traffic; lds_reads != 0 adds the
+ * GEMM's LDS fragment reads (8 per 16 matrix instructions).  sink: dev, workgroups * 256 floats
+ * (out, meaningless sums).  *flop (host, may be NULL) = workgroups * 4 * iters * 64 * 32768.
+ *
+ * emoe_measure_read_stream: grid-stride read of src (dev, `bytes` a multiple of 32768) with
+ * 16-byte loads, eight in flight per lane, nothing written.  sink: dev, 16 bytes.
+ *
+ * emoe_measure_copy_stream: plain copy of `bytes` (a multiple of 16) from src to dst (dev, not
+ * overlapping): reads and writes exactly `bytes`, the kernel of known traffic by which the
+ * readings of HBM traffic counters in the same profiler run are scaled.
+ */
+int emoe_measure_mfma_loop(const void *a, size_t a_elems, const void *b, size_t b_elems, int32_t lds_reads,
+                           int32_t workgroups, int32_t iters, float *sink, double *flop, void *stream);
+int emoe_measure_read_stream(const void *src, size_t bytes, int32_t workgroups, void *sink, void *stream);
+int emoe_measure_copy_stream(const void *src, void *dst, size_t bytes, int32_t workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

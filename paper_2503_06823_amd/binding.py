@@ -29,7 +29,8 @@ EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_rou
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
            "emoe_loader_residents", "emoe_loader_synchronize", "emoe_expected_latency", "emoe_schedule",
-           "emoe_generation_tick")
+           "emoe_generation_tick", "emoe_measure_mfma_loop", "emoe_measure_read_stream",
+           "emoe_measure_copy_stream")
 
 
 class EmoeLayerDesc(ctypes.Structure):
@@ -62,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.emoe_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.emoe_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.emoe_permute.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.emoe_measure_mfma_loop.argtypes = [vp, sz, vp, sz, i32, i32, i32, vp, vp, vp]
+        L.emoe_measure_read_stream.argtypes = [vp, sz, i32, vp, vp]
+        L.emoe_measure_copy_stream.argtypes = [vp, vp, sz, i32, vp]
         L.emoe_permute_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.emoe_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_expert_ffn_pass.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -153,6 +157,28 @@ def emoe_permute_static(desc, x, topk_expert, slot_of_expert, slot_counts, slot_
                                    _ptr(slot_counts), _ptr(slot_offsets), _ptr(perm), _ptr(inv_perm), _ptr(x_perm),
                                    _stream(stream))
     return _check(rc, "emoe_permute_static", check)
+
+
+def emoe_measure_mfma_loop(a, b, lds_reads: bool, workgroups: int, iters: int, sink, stream=None) -> float:
+    """Enqueues the matrix-instruction loop on the bf16 tensors a and b; returns the flop of the launch."""
+    flop = ctypes.c_double(0.0)
+    rc = lib().emoe_measure_mfma_loop(_ptr(a), ctypes.c_size_t(a.numel()), _ptr(b), ctypes.c_size_t(b.numel()),
+                                      ctypes.c_int32(1 if lds_reads else 0), ctypes.c_int32(workgroups),
+                                      ctypes.c_int32(iters), _ptr(sink), ctypes.byref(flop), _stream(stream))
+    _check(rc, "emoe_measure_mfma_loop", True)
+    return flop.value
+
+
+def emoe_measure_read_stream(src, nbytes: int, workgroups: int, sink, stream=None) -> int:
+    rc = lib().emoe_measure_read_stream(_ptr(src), ctypes.c_size_t(nbytes), ctypes.c_int32(workgroups), _ptr(sink),
+                                        _stream(stream))
+    return _check(rc, "emoe_measure_read_stream", True)
+
+
+def emoe_measure_copy_stream(src, dst, nbytes: int, workgroups: int, stream=None) -> int:
+    rc = lib().emoe_measure_copy_stream(_ptr(src), _ptr(dst), ctypes.c_size_t(nbytes), ctypes.c_int32(workgroups),
+                                        _stream(stream))
+    return _check(rc, "emoe_measure_copy_stream", True)
 
 
 def emoe_expert_ffn(desc, x_perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes, stream=None,

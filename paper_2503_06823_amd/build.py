@@ -17,7 +17,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libemoe.so")
 
 SOURCES = ["api.hip", "maps.hip", "select.hip", "loader.hip", "schedule.hip", "route.hip", "route_mfma.hip", "permute.hip", "combine.hip", "ffn_f32.hip", "ffn_bf16_tiled.hip", "ffn_bf16_mid.hip",
-           "ffn_bf16_stream.hip"]
+           "ffn_bf16_stream.hip", "peaks.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept out of all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

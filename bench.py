@@ -358,6 +358,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the upload measurement and the C5 / C2 workloads")
     ap.add_argument("--more-shapes", action="store_true",
                     help="also time a Mixtral-8x22B-shaped prefill layer, an OpenMoE-shaped layer and one short prompt at the Mixtral-8x7B shape")
+    ap.add_argument("--only", default="", help="time just this workload (C2, C5, X1 .. X5) and print its record: for profiler "
+                                               "runs of a workload that is not the headline")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = size the sample for about 15 s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run the library's plain copy kernel on 1 GiB, so that a hardware-counter run of this "
@@ -384,6 +386,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.only:
+        cfg = gen.CONFIGS.get(args.only) or gen.EXTRA_CONFIGS[args.only]
+        copies = {"C2": 4, "C4": 3, "X3": 3, "X5": 2}.get(args.only, 1)
+        print(json.dumps(other_config(torch, P, gen, cfg, args.steps, args.warmup, copies, cfg.name)), flush=True)
+        return
 
     # ---------------- prefill (headline) ----------------
     c3 = gen.C3

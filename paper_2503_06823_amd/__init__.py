@@ -8,5 +8,5 @@ from .binding import (EMOE_ACT_RELU, EMOE_ACT_SWIGLU, EMOE_BF16, EMOE_ERR_DEVICE
                       emoe_route, emoe_route_observe, emoe_expected_latency, emoe_schedule, emoe_generation_tick, make_request,
                       EmoeRequest, emoe_prompt_action, Loader, EMOE_PROMPT_REUSE, EMOE_PROMPT_LOAD_ALL,
                       EMOE_PROMPT_PREDICT, emoe_expected_tokens, emoe_select_experts, emoe_plan_load,
-                      emoe_workspace_bytes, lib, make_desc, status_string)
+                      emoe_workspace_bytes, lib, make_desc, make_event, status_string)
 from .layer import DeviceInputs, LayerBuffers, layer_forward

@@ -113,7 +113,21 @@ def _event(ev) -> ctypes.c_void_p:
         return ctypes.c_void_p(0)
     if isinstance(ev, int):
         return ctypes.c_void_p(ev)
-    return ctypes.c_void_p(ev.cuda_event)
+    handle = ev.cuda_event
+    if not handle:
+        # torch creates the HIP event at its first record(); before that there is no handle to pass, and
+        # a NULL would silently mean "no event"
+        raise ValueError("this torch event has no HIP event yet: create it with make_event(), or record it once")
+    return ctypes.c_void_p(handle)
+
+
+def make_event(timing: bool = False, stream=None):
+    """A torch event whose HIP event exists (recorded once on `stream`, default the current one), so that
+    it can be handed to the library as wait_event / done_event and be waited on or timed through torch."""
+    import torch
+    ev = torch.cuda.Event(enable_timing=timing)
+    ev.record(stream if stream is not None else torch.cuda.current_stream())
+    return ev
 
 
 def _check(rc: int, where: str, check: bool) -> int:

@@ -60,7 +60,7 @@ def test_load_then_forward_then_change_resident_set(gpu_device):
     mirror = np.full(S, -1, dtype=np.int32)
     side = torch.cuda.Stream()
     compute = torch.cuda.current_stream()
-    loaded, done = torch.cuda.Event(), torch.cuda.Event()
+    loaded, done = P.make_event(), P.make_event()     # events the library records and waits on: their handles must exist
     x, wg = to_dev(base.x, "bf16"), to_dev(base.w_gate, "bf16")
     buf = P.LayerBuffers.allocate(d)
     side.wait_stream(compute)   # the fills above run on the compute stream: order them before the first load

@@ -75,7 +75,7 @@ def test_observe_select_load_serve(gpu_device):
     eos = torch.full((S,), -1, dtype=torch.int32, device="cuda")
     mirror = np.full(S, -1, dtype=np.int32)
     side, compute = torch.cuda.Stream(), torch.cuda.current_stream()
-    loaded, done = torch.cuda.Event(), torch.cuda.Event()
+    loaded, done = P.make_event(), P.make_event()     # events the library records and waits on: their handles must exist
     x, wg, bias = to_dev(base.x, "bf16"), to_dev(base.w_gate, "bf16"), to_dev(base.gate_bias, "f32")
     buf = P.LayerBuffers.allocate(d)
     hist = torch.zeros(E, dtype=torch.int64, device="cuda")

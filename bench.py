@@ -76,6 +76,8 @@ def timed_steps(torch, P, dev, buf, steps, warmup, weight_sets):
     ws_n = buf.ffn_ws.numel()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
 
+    folded = d.k == 1     # one expert per token: the library folds the combine into the second product (one launch fewer)
+
     def step(i, events=None):
         w1, w3, w2 = weight_sets[i % len(weight_sets)]
         if events: events[0].record()
@@ -83,6 +85,12 @@ def timed_steps(torch, P, dev, buf, steps, warmup, weight_sets):
         P.emoe_permute(d, dev.x, buf.topk_expert, dev.slot_of_expert, buf.slot_counts, buf.slot_offsets, buf.perm,
                        buf.inv_perm, None, buf.permute_ws, buf.permute_ws.numel())     # indices only
         if events: events[1].record()
+        if folded:
+            P.emoe_expert_ffn_gather_combine(d, dev.x, buf.perm, buf.inv_perm, buf.slot_offsets, w1, w3, w2, buf.topk_weight,
+                                             None, buf.out, buf.ffn_ws, ws_n)
+            if events:
+                for e in events[2:]: e.record()
+            return
         # the FFN reads the token rows through perm (no x_perm copy)
         P.emoe_expert_ffn_gather_pass(d, 1, dev.x, buf.perm, buf.slot_offsets, w1, w3, w2, buf.y_perm, buf.ffn_ws, ws_n)
         if events: events[2].record()
@@ -99,11 +107,13 @@ def timed_steps(torch, P, dev, buf, steps, warmup, weight_sets):
         step(warmup + i, ev[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    names = ["route_permute", "ffn_pass1", "ffn_pass2", "combine"]
+    names = ["route_permute", "ffn_and_combine_folded", "-", "-"] if folded else ["route_permute", "ffn_pass1", "ffn_pass2", "combine"]
     ms = {n: sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j, n in enumerate(names)}
     for j, n in enumerate(names):     # median and minimum over the timed steps, per call
         v = sorted(e[j].elapsed_time(e[j + 1]) for e in ev)
         ms[n + "_median"], ms[n + "_min"] = v[len(v) // 2], v[0]
+    for key in [k for k in ms if k.startswith("-")]:
+        del ms[key]
     v = sorted(e[0].elapsed_time(e[4]) for e in ev)
     ms["step_median"], ms["step_min"] = v[len(v) // 2], v[0]
     return wall, ms
@@ -143,8 +153,8 @@ def graph_steps(torch, P, dev, buf, steps, warmup, weight_sets):
                 P.emoe_route(d, dev.x, dev.w_gate, dev.gate_bias, dev.slot_of_expert, buf.topk_expert, buf.topk_weight)
                 P.emoe_permute(d, dev.x, buf.topk_expert, dev.slot_of_expert, buf.slot_counts, buf.slot_offsets,
                                buf.perm, buf.inv_perm, None, buf.permute_ws, buf.permute_ws.numel())
-                P.emoe_expert_ffn_gather(d, dev.x, buf.perm, buf.slot_offsets, w1, w3, w2, buf.y_perm, buf.ffn_ws, ws_n)
-                P.emoe_combine(d, buf.y_perm, buf.inv_perm, buf.topk_weight, buf.out)
+                P.emoe_expert_ffn_gather_combine(d, dev.x, buf.perm, buf.inv_perm, buf.slot_offsets, w1, w3, w2,
+                                                 buf.topk_weight, buf.y_perm, buf.out, buf.ffn_ws, ws_n)
         graphs.append(g)
     torch.cuda.synchronize()
     for i in range(warmup):

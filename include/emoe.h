@@ -192,10 +192,25 @@ int emoe_combine(const emoe_layer_desc *desc, const void *y_perm, const int32_t 
                  const float *topk_weight, void *out, void *stream);
 
 /*
+ * emoe_expert_ffn_gather followed by emoe_combine as one call, with the combine folded into the
+ * second product where that costs nothing (Section 5.1: fewer global-memory reads): in a layer
+ * with one expert per token (k = 1) the gate weight is exactly 1 and the combine only undoes the
+ * row permutation, so the second product stores grouped row r straight into out[perm[r], :];
+ * y_perm is then neither written nor read (it may be NULL) and one launch is saved.  For k > 1 a
+ * token's k rows come from different output tiles and the call is the two calls as they are.
+ * The result in `out` is that of the two calls bit for bit.  Arguments as in the two calls.
+ */
+int emoe_expert_ffn_gather_combine(const emoe_layer_desc *desc, const void *x, const int32_t *perm,
+                                   const int32_t *inv_perm, const int32_t *slot_offsets, const void *w1_slots,
+                                   const void *w3_slots, const void *w2_slots, const float *topk_weight, void *y_perm,
+                                   void *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * The whole layer (Section 1: gate plus experts, here over the resident
- * experts only, Section 3.2.2): emoe_route, emoe_permute (indices only), emoe_expert_ffn_gather
- * and emoe_combine enqueued in this order on `stream`, with the same arguments, results and
- * errors as the four calls; nothing else is done and nothing is allocated.  All the intermediate
+ * experts only, Section 3.2.2): emoe_route, emoe_permute (indices only) and
+ * emoe_expert_ffn_gather_combine enqueued in this order on `stream`, with the same arguments,
+ * results and errors as the single calls; nothing else is done and nothing is allocated (with
+ * k = 1 y_perm stays unwritten, see emoe_expert_ffn_gather_combine).  All the intermediate
  * results are caller buffers as in the single calls (x_perm is not needed: the FFN reads the
  * token rows through perm).  Validation of all arguments happens before the first launch, so an
  * error leaves every output untouched.

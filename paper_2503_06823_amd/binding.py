@@ -24,7 +24,7 @@ ACTS = {"swiglu": EMOE_ACT_SWIGLU, "relu": EMOE_ACT_RELU}
 
 EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_route_observe", "emoe_permute",
            "emoe_permute_static",
-           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_combine",
+           "emoe_expert_ffn", "emoe_expert_ffn_pass", "emoe_expert_ffn_gather", "emoe_expert_ffn_gather_pass", "emoe_expert_ffn_gather_combine", "emoe_combine",
            "emoe_layer_forward", "emoe_load_experts", "emoe_expected_tokens",
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.emoe_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_expert_ffn_pass.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.emoe_expert_ffn_gather_combine.argtypes = [dp] + [vp] * 11 + [sz, vp]
         L.emoe_layer_forward.argtypes = [dp] + [vp] * 15 + [vp, sz, vp, sz, vp]
         L.emoe_load_experts.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in EXPORTS[1:]:
@@ -224,6 +225,14 @@ def emoe_expert_ffn_gather_pass(desc, which, x, perm, slot_offsets, w1_slots, w3
                                            _ptr(w1_slots), _ptr(w3_slots), _ptr(w2_slots), _ptr(y_perm), _ptr(ws),
                                            ctypes.c_size_t(int(ws_bytes)), _stream(stream))
     return _check(rc, "emoe_expert_ffn_gather_pass", check)
+
+
+def emoe_expert_ffn_gather_combine(desc, x, perm, inv_perm, slot_offsets, w1_slots, w3_slots, w2_slots, topk_weight,
+                                   y_perm, out, ws, ws_bytes, stream=None, check=True) -> int:
+    rc = lib().emoe_expert_ffn_gather_combine(ctypes.byref(desc), _ptr(x), _ptr(perm), _ptr(inv_perm), _ptr(slot_offsets),
+                                              _ptr(w1_slots), _ptr(w3_slots), _ptr(w2_slots), _ptr(topk_weight),
+                                              _ptr(y_perm), _ptr(out), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(rc, "emoe_expert_ffn_gather_combine", check)
 
 
 def emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream=None, check=True) -> int:

@@ -156,7 +156,7 @@ int emoe_permute(const emoe_layer_desc* desc, const void* x, const int32_t* topk
 }
 
 static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void* x_perm, const int32_t* perm,
-                             const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
+                             const int32_t* out_perm, const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
                              const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
     int rc = validate_desc(desc);
     if (rc != EMOE_OK) return rc;
@@ -166,7 +166,7 @@ static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void
     if (!ws || ws_bytes < ffn_ws_layout(*desc).total) return EMOE_ERR_WORKSPACE;
     if (desc->T == 0) return EMOE_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const RowGather gather{perm, desc->k, desc->T};  // perm == nullptr: x_perm holds the grouped rows themselves
+    const RowGather gather{perm, desc->k, desc->T, out_perm};  // perm == nullptr: x_perm holds the grouped rows themselves
     hipError_t e;
     if (desc->dtype == EMOE_F32)
         e = launch_ffn_f32(*desc, x_perm, gather, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, passes, st);
@@ -182,7 +182,7 @@ static int expert_ffn_passes(const emoe_layer_desc* desc, int passes, const void
 int emoe_expert_ffn(const emoe_layer_desc* desc, const void* x_perm, const int32_t* slot_offsets,
                     const void* w1_slots, const void* w3_slots, const void* w2_slots, void* y_perm, void* ws,
                     size_t ws_bytes, void* stream) {
-    return expert_ffn_passes(desc, 3, x_perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+    return expert_ffn_passes(desc, 3, x_perm, nullptr, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
                              stream);
 }
 
@@ -190,7 +190,7 @@ int emoe_expert_ffn_pass(const emoe_layer_desc* desc, int32_t pass, const void* 
                          const void* w1_slots, const void* w3_slots, const void* w2_slots, void* y_perm, void* ws,
                          size_t ws_bytes, void* stream) {
     if (pass != 1 && pass != 2) return EMOE_ERR_SHAPE;
-    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x_perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots,
+    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x_perm, nullptr, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots,
                              y_perm, ws, ws_bytes, stream);
 }
 
@@ -198,7 +198,7 @@ int emoe_expert_ffn_gather(const emoe_layer_desc* desc, const void* x, const int
                            const int32_t* slot_offsets, const void* w1_slots, const void* w3_slots,
                            const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
     if (!perm) return EMOE_ERR_NULL;
-    return expert_ffn_passes(desc, 3, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+    return expert_ffn_passes(desc, 3, x, perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
                              stream);
 }
 
@@ -207,8 +207,24 @@ int emoe_expert_ffn_gather_pass(const emoe_layer_desc* desc, int32_t pass, const
                                 const void* w2_slots, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
     if (pass != 1 && pass != 2) return EMOE_ERR_SHAPE;
     if (!perm) return EMOE_ERR_NULL;
-    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws,
+    return expert_ffn_passes(desc, pass == 1 ? 1 : 2, x, perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws,
                              ws_bytes, stream);
+}
+
+int emoe_expert_ffn_gather_combine(const emoe_layer_desc* desc, const void* x, const int32_t* perm,
+                                   const int32_t* inv_perm, const int32_t* slot_offsets, const void* w1_slots,
+                                   const void* w3_slots, const void* w2_slots, const float* topk_weight, void* y_perm,
+                                   void* out, void* ws, size_t ws_bytes, void* stream) {
+    if (!perm || !inv_perm || !topk_weight || !out) return EMOE_ERR_NULL;
+    if (desc != nullptr && desc->k == 1)
+        // one expert per token: its gate weight is exactly 1 and the combine is the inverse of the row
+        // permutation, so the second product stores row r as out[perm[r]] and the fifth launch disappears
+        return expert_ffn_passes(desc, 3, x, perm, perm, slot_offsets, w1_slots, w3_slots, w2_slots, out, ws, ws_bytes, stream);
+    if (!y_perm) return EMOE_ERR_NULL;
+    int rc = expert_ffn_passes(desc, 3, x, perm, nullptr, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ws, ws_bytes,
+                               stream);
+    if (rc != EMOE_OK) return rc;
+    return emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream);
 }
 
 int emoe_combine(const emoe_layer_desc* desc, const void* y_perm, const int32_t* inv_perm, const float* topk_weight,
@@ -241,10 +257,8 @@ int emoe_layer_forward(const emoe_layer_desc* desc, const void* x, const void* w
     rc = emoe_permute(desc, x, topk_expert, slot_of_expert, slot_counts, slot_offsets, perm, inv_perm, nullptr, permute_ws,
                       permute_ws_bytes, stream);
     if (rc != EMOE_OK) return rc;
-    rc = emoe_expert_ffn_gather(desc, x, perm, slot_offsets, w1_slots, w3_slots, w2_slots, y_perm, ffn_ws, ffn_ws_bytes,
-                                stream);
-    if (rc != EMOE_OK) return rc;
-    return emoe_combine(desc, y_perm, inv_perm, topk_weight, out, stream);
+    return emoe_expert_ffn_gather_combine(desc, x, perm, inv_perm, slot_offsets, w1_slots, w3_slots, w2_slots, topk_weight,
+                                          y_perm, out, ffn_ws, ffn_ws_bytes, stream);
 }
 
 int emoe_load_experts(const emoe_layer_desc* desc, int32_t n, const int32_t* expert_ids, const int32_t* slot_ids,

@@ -69,10 +69,14 @@ hipError_t launch_combine(const emoe_layer_desc& d, const void* y_perm, const in
                           const float* topk_weight, void* out, hipStream_t st);
 // Where pass 1 finds the token row of grouped row r: in x_perm[r] (perm == nullptr), or in
 // x[perm[r] / k] (the gather folded into the operand load; `rows` = T bounds the buffer).
+// out_perm (pass 2 only): nullptr, or, with the combine folded into the second product of a layer
+// with one expert per token, the permutation by which result row r is stored as row out_perm[r] of
+// the output (the token it belongs to) instead of row r.
 struct RowGather {
     const int32_t* perm;
     int k;
     int rows;
+    const int32_t* out_perm;
 };
 
 hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, RowGather gather, const int32_t* offsets, const void* w1,

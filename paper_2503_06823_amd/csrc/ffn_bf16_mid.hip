@@ -455,7 +455,11 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
         for (int it = 0; it < BM / NW / RPS; ++it) {
             const int r = wave * (BM / NW) + it * RPS + lane / CPR;
             const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & SWM)) * 16));
-            if (row0 + r < row_end && n < N) *reinterpret_cast<uint4*>(c + (size_t)(row0 + r) * N + n) = val;
+            if (row0 + r < row_end && n < N) {
+                // combine folded in (second product, one expert per token): the row goes to its token's row of the output
+                const int dr = (EPI == kPlain && gather.out_perm != nullptr) ? gather.out_perm[row0 + r] : row0 + r;
+                *reinterpret_cast<uint4*>(c + (size_t)dr * N + n) = val;
+            }
         }
         __syncthreads();  // the image is read: the next trip's loads may overwrite it
     }
@@ -468,6 +472,7 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
 // took whole tiles, which the host cannot know, every workgroup exits after reading slot_offsets.
 template <int EPI, int BM, int BR>
 __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
+                                                 const int32_t* __restrict__ out_perm,
                                                  const float* __restrict__ partials, int S, int N, int K,
                                                  int n_tiles, int G) {
     constexpr int WM = BM / 64, WN = NW / WM;  // as in the main kernel
@@ -513,7 +518,7 @@ __global__ __launch_bounds__(64 * NW) void mid_fixup(const int32_t* __restrict__
         // a lane holds token lane % 32 of its block and weight rows 8 gq + 4 (lane / 32) + 0..3
         const int r = row0 + wm * 64 + mi * 32 + (lane & 31);
         if (r >= row_end) continue;
-        bf16_t* crow = c + (size_t)r * N;
+        bf16_t* crow = c + (size_t)((EPI == kPlain && out_perm != nullptr) ? out_perm[r] : r) * N;
         const int col0 = nt * BNO + wn * (BNO / WN) + ni * 32 + (lane >> 5) * 4;
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
@@ -551,7 +556,7 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
     const int n_tiles = (N + BNO - 1) / BNO;
     if (PERSIST) {
         kern<<<kGroups, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
-        mid_fixup<EPI, BM, BR><<<kGroups - 1, 64 * NW, 0, st>>>(offsets, c, partials, S, N, K, n_tiles, kGroups);
+        mid_fixup<EPI, BM, BR><<<kGroups - 1, 64 * NW, 0, st>>>(offsets, c, gather.out_perm, partials, S, N, K, n_tiles, kGroups);
     } else {
         const long long tiles = m_tiles * n_tiles;
         const unsigned blocks = (unsigned)((tiles + XCDS - 1) / XCDS * XCDS);
@@ -626,7 +631,7 @@ hipError_t launch_ffn_bf16_mid(const emoe_layer_desc& d, const void* x_perm, Row
         e = launch_one<kRelu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), nullptr, h, partials, A, d.S, d.d_ff,
                               d.d_model, st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const bf16_t*>(w2), nullptr,
+    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0, gather.out_perm}, offsets, static_cast<const bf16_t*>(w2), nullptr,
                               static_cast<bf16_t*>(y_perm), partials, A, d.S, d.d_model, d.d_ff, st);
 }
 

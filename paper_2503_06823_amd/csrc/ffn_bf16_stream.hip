@@ -208,6 +208,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
             // lane holds token lane%32 and weight rows 8g + 4*(lane/32) + 0..3 of each 32-row block
             const int r = tok0 + (lane & 31);
             if (r < row_end) {
+                const int dr = (EPI == kPlain && gather.out_perm != nullptr) ? gather.out_perm[r] : r;  // combine folded in: the token's row
 #pragma unroll
                 for (int blk = 0; blk < (EPI == kSwiglu ? 1 : NBLK); ++blk) {
 #pragma unroll
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_bf16(const bf16_t* __restr
                             if (EPI == kRelu) tv = fmaxf(tv, 0.0f);
                             v[q] = tv;
                         }
-                        *reinterpret_cast<bf16x4*>(c + (size_t)r * N + nn) = __builtin_convertvector(v, bf16x4);
+                        *reinterpret_cast<bf16x4*>(c + (size_t)dr * N + nn) = __builtin_convertvector(v, bf16x4);
                     }
                 }
             }
@@ -270,7 +271,7 @@ hipError_t launch_ffn_bf16_stream(const emoe_layer_desc& d, const void* x_perm, 
     else
         e = launch_one<kRelu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), nullptr, h, d.S, d.d_ff, d.d_model, st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm), d.S,
+    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0, gather.out_perm}, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm), d.S,
                               d.d_model, d.d_ff, st);
 }
 

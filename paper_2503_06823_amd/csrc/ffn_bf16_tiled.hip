@@ -204,12 +204,12 @@ __device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets,
 // A lane holds token lane%32 and weight rows 8g + 4*(lane/32) + 0..3.
 template <int EPI>
 __device__ __forceinline__ void epilogue_block(const floatx16& gate, const floatx16& up, bf16_t* __restrict__ c,
-                                               int row0, int row_end, int n0, int N, int wm, int wn, int mi, int ni,
-                                               int lane) {
+                                               const int32_t* __restrict__ out_perm, int row0, int row_end, int n0, int N,
+                                               int wm, int wn, int mi, int ni, int lane) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     const int r = row0 + tile_block(wm, mi) * 32 + (lane & 31);
     if (r >= row_end) return;
-    bf16_t* crow = c + (size_t)r * N;
+    bf16_t* crow = c + (size_t)((EPI == kPlain && out_perm != nullptr) ? out_perm[r] : r) * N;
     const int col0 = n0 + wn * (BNO / WN) + ni * 32 + (lane >> 5) * 4;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -290,7 +290,8 @@ __device__ __forceinline__ float acc_read(float a) {
 // 16-byte reads (nearly) free of bank conflicts.  All DMA loads have landed and all fragment reads
 // are done when this runs; the barrier at the end keeps the next tile's loads off the image.
 template <int EPI>
-__device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c, char* lds, int row0,
+__device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __restrict__ c,
+                                         const int32_t* __restrict__ out_perm, char* lds, int row0,
                                          int row_end, int n0, int N, int wm, int wn, int wave, int lane) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;
     constexpr int NB = EPI == kSwiglu ? WB / 2 : WB;
@@ -329,7 +330,11 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __rest
     for (int it = 0; it < 64 / RPS; ++it) {
         const int r = wave * 64 + it * RPS + lane / CPR;
         const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & 15)) * 16));
-        if (row0 + r < row_end && n < N) *reinterpret_cast<uint4*>(c + (size_t)(row0 + r) * N + n) = val;
+        if (row0 + r < row_end && n < N) {
+            // combine folded in (second product, one expert per token): the row goes to its token's row of the output
+            const int dr = (EPI == kPlain && out_perm != nullptr) ? out_perm[row0 + r] : row0 + r;
+            *reinterpret_cast<uint4*>(c + (size_t)dr * N + n) = val;
+        }
     }
     __syncthreads();
 }
@@ -612,7 +617,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         barrier_keep_loads<0>();
 
         if (piece < 0) {
-            epilogue<EPI>(acc, c, lds, row0, row_end, n0, N, wm, wn, wave, lane);
+            epilogue<EPI>(acc, c, gather.out_perm, lds, row0, row_end, n0, N, wm, wn, wave, lane);
         } else {  // a K piece of a leftover tile: raw accumulators to the workspace, [register][thread]
             float* dst = partials + kPlanFloats + (size_t)piece * (BM * BR) + tid;
 #pragma unroll
@@ -634,6 +639,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
 // which the host cannot know, every workgroup exits after one load.
 template <int EPI>
 __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
+                                                        const int32_t* __restrict__ out_perm,
                                                         const int* __restrict__ hdr,
                                                         const float* __restrict__ partials, int S, int N, int K,
                                                         int n_tiles, int G) {
@@ -669,7 +675,7 @@ __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restric
             up[v] += w[v];
         }
     }
-    epilogue_block<EPI>(gate, up, c, row0, row_end, nt * BNO, N, wave / WN, wave % WN, mi, ni, lane);
+    epilogue_block<EPI>(gate, up, c, out_perm, row0, row_end, nt * BNO, N, wave / WN, wave % WN, mi, ni, lane);
 }
 
 template <int EPI, bool KTAIL>
@@ -684,7 +690,7 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
         attr_set.store(true, std::memory_order_release);
     }
     kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
-    splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, reinterpret_cast<const int*>(partials),
+    splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, gather.out_perm, reinterpret_cast<const int*>(partials),
                                                         partials + kPlanFloats, S, N, K, n_tiles, kPersistentGroups);
     return hipGetLastError();
 }
@@ -717,7 +723,7 @@ hipError_t launch_ffn_bf16_tiled(const emoe_layer_desc& d, const void* x_perm, R
         e = launch_one<kRelu>(xp, gather, offsets, static_cast<const bf16_t*>(w1), nullptr, h, partials, d.S, d.d_ff, d.d_model,
                               st);
     if (e != hipSuccess || !(passes & 2)) return e;
-    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm),
+    return launch_one<kPlain>(h, RowGather{nullptr, 1, 0, gather.out_perm}, offsets, static_cast<const bf16_t*>(w2), nullptr, static_cast<bf16_t*>(y_perm),
                               partials, d.S, d.d_model, d.d_ff, st);
 }
 

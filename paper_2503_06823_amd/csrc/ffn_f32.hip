@@ -87,6 +87,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict_
     for (int i = 0; i < 4; ++i) {
         const int r = row0 + ty * 4 + i;
         if (r >= row_end) continue;
+        const int dr = (EPI == kPlain && gather.out_perm != nullptr) ? gather.out_perm[r] : r;  // combine folded in: the token's row
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict_
             float v = acc0[i][j];
             if (EPI == kSwiglu) v = v / (1.0f + expf(-v)) * acc1[i][j];
             if (EPI == kRelu) v = fmaxf(v, 0.0f);
-            c[(size_t)r * N + n] = v;
+            c[(size_t)dr * N + n] = v;
         }
     }
 }
@@ -116,7 +117,7 @@ hipError_t launch_ffn_f32(const emoe_layer_desc& d, const void* x_perm, RowGathe
         grouped_gemm_f32<kRelu><<<g1, 256, 0, st>>>(xp, gather, offsets, static_cast<const float*>(w1), nullptr, h, d.S,
                                                     d.d_ff, d.d_model);
     if (passes & 2)
-        grouped_gemm_f32<kPlain><<<g2, 256, 0, st>>>(h, RowGather{nullptr, 1, 0}, offsets, static_cast<const float*>(w2), nullptr,
+        grouped_gemm_f32<kPlain><<<g2, 256, 0, st>>>(h, RowGather{nullptr, 1, 0, gather.out_perm}, offsets, static_cast<const float*>(w2), nullptr,
                                                      static_cast<float*>(y_perm), d.S, d.d_model, d.d_ff);
     return hipGetLastError();
 }

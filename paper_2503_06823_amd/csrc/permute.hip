@@ -162,71 +162,62 @@ __global__ __launch_bounds__(kThreads) void place_kernel(const int32_t* __restri
     }
 }
 
-// count + scan + place in one workgroup, for A <= kPermuteChunk (a decode step): two launches fewer.
-__global__ __launch_bounds__(kThreads) void sort_small_kernel(const int32_t* __restrict__ topk_expert,
-                                                              const int32_t* __restrict__ slot_of_expert,
-                                                              int32_t* __restrict__ slot_counts,
-                                                              int32_t* __restrict__ slot_offsets,
-                                                              int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
-                                                              int A, int E, int S) {
-    __shared__ int cnt[kMaxExperts];
-    __shared__ int running[kMaxExperts];
-    __shared__ int wave_cnt[kThreads / 64][kMaxExperts];
+// count + scan + place in one workgroup, for A <= kPermuteChunk (a decode step, a short prompt): two
+// launches fewer.  One thread per assignment (16 wavefronts), one pass: every wavefront ranks its 64
+// assignments per slot with ballots, wavefront 0 turns the 16 x S counts into the slots' offsets, and
+// each assignment's row is its slot's offset + the counts of the wavefronts before its own + its rank.
+constexpr int kSmallThreads = kPermuteChunk;
+constexpr int kSmallWaves = kSmallThreads / 64;
+__global__ __launch_bounds__(kSmallThreads) void sort_small_kernel(const int32_t* __restrict__ topk_expert,
+                                                                   const int32_t* __restrict__ slot_of_expert,
+                                                                   int32_t* __restrict__ slot_counts,
+                                                                   int32_t* __restrict__ slot_offsets,
+                                                                   int32_t* __restrict__ perm,
+                                                                   int32_t* __restrict__ inv_perm, int A, int E, int S) {
+    __shared__ int wave_cnt[kSmallWaves][kMaxExperts];  // [wavefront][slot]: count, then the first row of that wavefront's share
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    if (threadIdx.x < kMaxExperts) cnt[threadIdx.x] = 0;
-    __syncthreads();
-    int keys[kPasses];
-#pragma unroll
-    for (int p = 0; p < kPasses; ++p) {
-        keys[p] = key_of(topk_expert, slot_of_expert, p * kThreads + threadIdx.x, A, E, S);
-        if (keys[p] >= 0) atomicAdd(&cnt[keys[p]], 1);
+    const int a = threadIdx.x;
+    const int key = key_of(topk_expert, slot_of_expert, a, A, E, S);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int rank = 0, mine = 0;  // lane s ends up with this wavefront's count for slot s
+    for (int s = 0; s < S; ++s) {
+        const unsigned long long m = __ballot(key == s);
+        if (key == s) rank = __popcll(m & below);
+        if (lane == s) mine = __popcll(m);
     }
+    wave_cnt[wave][lane] = mine;
     __syncthreads();
-    if (wave == 0) {  // exclusive prefix over the slots
-        const int c = lane < S ? cnt[lane] : 0;
+    if (wave == 0) {  // lane = slot: total, exclusive prefix over the slots, then the start of every wavefront's share
+        int c = 0;
+#pragma unroll
+        for (int w = 0; w < kSmallWaves; ++w) c += wave_cnt[w][lane];
         int incl = c;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            int up = __shfl_up(incl, off);
+            const int up = __shfl_up(incl, off);
             if (lane >= off) incl += up;
         }
         if (lane < S) {
             slot_counts[lane] = c;
             slot_offsets[lane] = incl - c;
-            running[lane] = incl - c;
         }
         if (lane == S - 1) slot_offsets[S] = incl;
-    }
-    const unsigned long long below = (1ull << lane) - 1ull;
-    for (int p = 0; p < kPasses; ++p) {
-        if (p * kThreads >= A) break;  // uniform
-        const int a = p * kThreads + threadIdx.x;
-        const int key = keys[p];
-        int rank = 0, mine = 0;
-        for (int s = 0; s < S; ++s) {
-            unsigned long long m = __ballot(key == s);
-            if (key == s) rank = __popcll(m & below);
-            if (lane == s) mine = __popcll(m);
-        }
-        wave_cnt[wave][lane] = mine;
-        __syncthreads();
-        if (key >= 0) {
-            int r = running[key] + rank;
-            for (int w = 0; w < wave; ++w) r += wave_cnt[w][key];
-            perm[r] = a;
-            inv_perm[a] = r;
-        } else if (a < A) {
-            inv_perm[a] = -1;
-        }
-        __syncthreads();
-        if (threadIdx.x < S) {
-            int add = 0;
+        int run = incl - c;
 #pragma unroll
-            for (int w = 0; w < kThreads / 64; ++w) add += wave_cnt[w][threadIdx.x];
-            running[threadIdx.x] += add;
+        for (int w = 0; w < kSmallWaves; ++w) {
+            const int n = wave_cnt[w][lane];
+            wave_cnt[w][lane] = run;
+            run += n;
         }
-        __syncthreads();
+    }
+    __syncthreads();
+    if (key >= 0) {
+        const int r = wave_cnt[wave][key] + rank;
+        perm[r] = a;
+        inv_perm[a] = r;
+    } else if (a < A) {
+        inv_perm[a] = -1;
     }
 }
 
@@ -257,7 +248,7 @@ hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t
     const int n_blocks = (A + kPermuteChunk - 1) / kPermuteChunk;
     int32_t* block_counts = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(ws) + permute_ws_layout(d).block_counts);
     if (n_blocks == 1) {
-        sort_small_kernel<<<1, kThreads, 0, st>>>(topk_expert, slot_of_expert, counts, offsets, perm, inv_perm, A, d.E,
+        sort_small_kernel<<<1, kSmallThreads, 0, st>>>(topk_expert, slot_of_expert, counts, offsets, perm, inv_perm, A, d.E,
                                                   d.S);
     } else {
         count_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, A, d.E, d.S);

@@ -11,6 +11,7 @@ import torch
 
 import emoe_inputs as gen
 import oracle
+import paper_2503_06823_amd as P
 from gpu_util import DeviceLayer, check_ffn_rows, check_outputs, check_routing_and_permutation, stratified_rows
 
 pytestmark = pytest.mark.gpu
@@ -47,3 +48,11 @@ def test_full_size_workload(gpu_device, name):
     tw = dl.buf.topk_weight
     assert torch.allclose(tw.sum(dim=1), torch.ones(cfg.T, device=tw.device), atol=1e-5)
     dl.check_gather_path_is_identical()       # the configuration bench.py times reads x through perm
+    if cfg.k == 1:                             # ... and, with one expert per token, folds the combine into the second product
+        b = dl.buf
+        separate = b.out.clone()
+        b.out.zero_()
+        P.emoe_expert_ffn_gather_combine(dl.desc, dl.x, b.perm, b.inv_perm, b.slot_offsets, dl.w1, dl.w3, dl.w2,
+                                         b.topk_weight, None, b.out, b.ffn_ws, b.ffn_ws.numel())
+        torch.cuda.synchronize()
+        assert torch.equal(b.out, separate)

@@ -230,6 +230,54 @@ def test_random_layers_with_a_long_k(gpu_device, c):
     dl.check_gather_path_is_identical()
 
 
+# one expert per token on every FFN path: fp32, streaming, tiles of 64 / 128 / 256 token rows, whole and cut along K
+TOP1_CASES = [c for c in SMALL_CASES if c.k == 1] + [
+    cfg("tiled_top1_splitk", T=1600, d_model=1032, d_ff=1160, E=8, k=1, R=4, index=80),
+    cfg("tiled_top1_swiglu_ragged", T=900, d_model=328, d_ff=456, E=8, k=1, R=3, S=4, index=81),
+    cfg("mid_top1_swiglu", T=200, d_model=256, d_ff=384, E=8, k=1, R=4, index=82),
+]
+
+
+@pytest.mark.parametrize("c", TOP1_CASES, ids=lambda c: c.name)
+def test_combine_folded_into_the_second_product(gpu_device, c):
+    """k = 1: emoe_expert_ffn_gather_combine stores the second product's rows straight into `out`;
+    bit for bit the result of emoe_expert_ffn_gather + emoe_combine, which the other tests compare
+    with the oracle (and here once more)."""
+    inp = gen.make_layer_inputs(c, shuffle_slots=c.slots > 1)
+    ref = oracle.layer_forward(inp)
+    dl = DeviceLayer(inp)
+    dl.forward(gather_in_ffn=True)
+    torch.cuda.synchronize()
+    check_outputs(dl, ref)
+    b, d = dl.buf, dl.desc
+    separate = b.out.clone()
+    b.out.fill_(float("nan"))
+    y_before = b.y_perm.clone()
+    P.emoe_expert_ffn_gather_combine(d, dl.x, b.perm, b.inv_perm, b.slot_offsets, dl.w1, dl.w3, dl.w2, b.topk_weight, None,
+                                     b.out, b.ffn_ws, b.ffn_ws.numel())
+    torch.cuda.synchronize()
+    assert torch.equal(b.out.view(torch.int16) if b.out.dtype == torch.bfloat16 else b.out,
+                       separate.view(torch.int16) if separate.dtype == torch.bfloat16 else separate)
+    assert torch.equal(b.y_perm, y_before), "y_perm must stay untouched when the combine is folded in"
+
+
+def test_folded_combine_with_several_experts_per_token_is_the_two_calls(gpu_device):
+    c = [c for c in SMALL_CASES if c.name == "mid_swiglu_ragged"][0]
+    dl = DeviceLayer(gen.make_layer_inputs(c))
+    dl.forward(gather_in_ffn=True)
+    torch.cuda.synchronize()
+    b = dl.buf
+    separate = b.out.clone()
+    b.out.zero_(); b.y_perm.zero_()
+    P.emoe_expert_ffn_gather_combine(dl.desc, dl.x, b.perm, b.inv_perm, b.slot_offsets, dl.w1, dl.w3, dl.w2, b.topk_weight,
+                                     b.y_perm, b.out, b.ffn_ws, b.ffn_ws.numel())
+    torch.cuda.synchronize()
+    assert torch.equal(b.out, separate)
+    rc = P.emoe_expert_ffn_gather_combine(dl.desc, dl.x, b.perm, b.inv_perm, b.slot_offsets, dl.w1, dl.w3, dl.w2,
+                                          b.topk_weight, None, b.out, b.ffn_ws, b.ffn_ws.numel(), check=False)
+    assert rc == P.EMOE_ERR_NULL        # with k > 1 y_perm is needed
+
+
 @pytest.mark.parametrize("name", ["mid_swiglu_ragged", "tiled_relu_skewed", "stream_decode", "C1_tiny_f32"])
 def test_layer_forward_in_one_call_equals_the_four_calls(gpu_device, name):
     c = [c for c in SMALL_CASES if c.name == name][0]
@@ -239,6 +287,8 @@ def test_layer_forward_in_one_call_equals_the_four_calls(gpu_device, name):
     P.layer_forward(b.buf, b.x, b.w_gate, b.gate_bias, b.slot_of_expert, b.w1, b.w3, b.w2, one_call=True)
     torch.cuda.synchronize()
     for f in ("topk_expert", "topk_weight", "slot_counts", "slot_offsets", "perm", "inv_perm", "y_perm", "out"):
+        if f == "y_perm" and c.k == 1:
+            continue        # one expert per token: the second product writes `out` directly, y_perm stays unwritten
         assert torch.equal(getattr(a.buf, f), getattr(b.buf, f)), f
     # an argument error is found before anything is enqueued: outputs stay as they are
     before = b.buf.out.clone()

@@ -181,6 +181,32 @@ def miss_rate(torch, P, dev, buf):
     return float((dev.slot_of_expert[free.long()] < 0).float().mean())
 
 
+def combine_by_scatter(torch, P, buf):
+    """Section 5.1 argues with global-memory reads, and folding the combine into the second product would spare
+    the y_perm round trip; with several experts per token that needs atomics.  Times the combine kernel against
+    the same combine done that way (clear an fp32 image, add every grouped row into it with atomics, convert):
+    a lower bound of what the fold costs, since the second product's own work is not even included."""
+    d = buf.desc
+    image = torch.empty((d.T, d.d_model), dtype=torch.float32, device="cuda")
+    out2 = torch.empty_like(buf.out)
+    def timed(fn, n=12):
+        for _ in range(3): fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record()
+        for i in range(n):
+            fn(); ev[i + 1].record()
+        torch.cuda.synchronize()
+        return sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2] * 1e3
+    t_combine = timed(lambda: P.emoe_combine(d, buf.y_perm, buf.inv_perm, buf.topk_weight, buf.out))
+    t_scatter = timed(lambda: P.emoe_measure_scatter_combine(d, buf.y_perm, buf.perm, buf.topk_weight, image, out2))
+    diff = float((out2.float() - buf.out.float()).abs().max())
+    el = 2
+    return {"combine_kernel_us": t_combine, "clear_scatter_add_convert_us": t_scatter, "max_abs_difference": diff,
+            "combine_bytes": (d.T * d.k + d.T) * d.d_model * el,
+            "scatter_bytes_beside_the_second_product": d.T * d.d_model * (4 + 4 * d.k + 4 + el),
+            "y_perm_bytes_the_fold_would_spare": 2 * d.T * d.k * d.d_model * el}
+
+
 def measure_ceilings(torch, P, x, w, read_buffers):
     """What this GPU sustains on the two resources that bound the FFN, with kernels that do nothing else:
     the matrix-instruction loop on the workload's own operand values (no global traffic) and a plain
@@ -232,6 +258,7 @@ def layer_work(cfg, counts):
 def other_config(torch, P, gen, cfg, steps, warmup, copies, label, graph=False):
     _, wall, ms, counts, dev, buf = run_workload(torch, P, gen, cfg, steps, warmup, copies, graph=graph)
     missed = miss_rate(torch, P, dev, buf)
+    fold = combine_by_scatter(torch, P, buf) if (cfg.k > 1 and cfg.dtype == "bf16") else None
     del dev, buf
     torch.cuda.empty_cache()
     flop, wbytes = layer_work(cfg, counts)
@@ -243,7 +270,7 @@ def other_config(torch, P, gen, cfg, steps, warmup, copies, label, graph=False):
     log(f"{cfg.name}: {t * 1e3:.3f} ms/step, miss rate {missed:.3f}, breakdown {ms}")
     return {"config": {"workload": label, "rows_per_slot_max": int(counts.max()), "slots_with_rows": int((counts > 0).sum())},
             "value": cfg.T / t, "unit": "tokens/s", "ms_per_step": t * 1e3, "steps": steps, "breakdown_ms": ms,
-            "miss_rate": missed, **extra,
+            "miss_rate": missed, **extra, **({"combine_fold_measurement": fold} if fold else {}),
             "layer_tflops": flop / t / 1e12, "layer_mfma_frac": flop / t / 1e12 / PEAK_BF16_MFMA_TFLOPS,
             "layer_weight_gbs": wbytes / t / 1e9, "layer_hbm_frac": wbytes / t / 1e9 / PEAK_HBM_GBS}
 
@@ -400,7 +427,8 @@ def main():
     if args.only:
         cfg = gen.CONFIGS.get(args.only) or gen.EXTRA_CONFIGS[args.only]
         copies = {"C2": 4, "C4": 3, "X3": 3, "X5": 2}.get(args.only, 1)
-        print(json.dumps(other_config(torch, P, gen, cfg, args.steps, args.warmup, copies, cfg.name)), flush=True)
+        print(json.dumps(other_config(torch, P, gen, cfg, args.steps, args.warmup, copies, cfg.name,
+                                      graph=args.only in ("C2", "C4", "X3", "X5"))), flush=True)
         return
 
     # ---------------- prefill (headline) ----------------
@@ -430,6 +458,7 @@ def main():
     log(f"prefill: {ms_step:.3f} ms/step, {tokens_s:,.0f} tokens/s, pass1 {tf1:.0f} TFLOP/s, breakdown {ms}")
 
     result["prefill_miss_rate"] = miss_rate(torch, P, dev3, buf3)
+    result["combine_fold_measurement"] = combine_by_scatter(torch, P, buf3)
     ceilings = None
     if not args.no_ceilings:
         # measured ceilings beside the datasheet peaks: the matrix-instruction loop on this layer's own token rows

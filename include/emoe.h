@@ -423,6 +423,18 @@ int emoe_measure_mfma_loop(const void *a, size_t a_elems, const void *b, size_t 
 int emoe_measure_read_stream(const void *src, size_t bytes, int32_t workgroups, void *sink, void *stream);
 int emoe_measure_copy_stream(const void *src, void *dst, size_t bytes, int32_t workgroups, void *stream);
 
+/*
+ * emoe_measure_scatter_combine: emoe_combine computed the way a second product with the combine
+ * folded into its epilogue would have to compute it for k > 1: an fp32 image of the output is
+ * cleared, every grouped row is added into its token's row with atomics (weighted by its gate
+ * weight), and the image is converted to bf16.  Same inputs as emoe_combine except that rows are
+ * found through perm [A] (grouped row -> assignment) and `image` [T,d] fp32 dev is scratch.  bf16
+ * layers only.  The sum's order is that of the atomics: for k = 2 the result is reproducible,
+ * beyond that it is not.  Exists to measure the cost of that design against emoe_combine.
+ */
+int emoe_measure_scatter_combine(const emoe_layer_desc *desc, const void *y_perm, const int32_t *perm,
+                                 const float *topk_weight, float *image, void *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_rou
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
            "emoe_loader_residents", "emoe_loader_synchronize", "emoe_expected_latency", "emoe_schedule",
            "emoe_generation_tick", "emoe_measure_mfma_loop", "emoe_measure_read_stream",
-           "emoe_measure_copy_stream")
+           "emoe_measure_copy_stream", "emoe_measure_scatter_combine")
 
 
 class EmoeLayerDesc(ctypes.Structure):
@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.emoe_measure_mfma_loop.argtypes = [vp, sz, vp, sz, i32, i32, i32, vp, vp, vp]
         L.emoe_measure_read_stream.argtypes = [vp, sz, i32, vp, vp]
         L.emoe_measure_copy_stream.argtypes = [vp, vp, sz, i32, vp]
+        L.emoe_measure_scatter_combine.argtypes = [dp, vp, vp, vp, vp, vp, vp]
         L.emoe_permute_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.emoe_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.emoe_expert_ffn_pass.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -188,6 +189,12 @@ def emoe_measure_read_stream(src, nbytes: int, workgroups: int, sink, stream=Non
     rc = lib().emoe_measure_read_stream(_ptr(src), ctypes.c_size_t(nbytes), ctypes.c_int32(workgroups), _ptr(sink),
                                         _stream(stream))
     return _check(rc, "emoe_measure_read_stream", True)
+
+
+def emoe_measure_scatter_combine(desc, y_perm, perm, topk_weight, image, out, stream=None) -> int:
+    rc = lib().emoe_measure_scatter_combine(ctypes.byref(desc), _ptr(y_perm), _ptr(perm), _ptr(topk_weight), _ptr(image),
+                                            _ptr(out), _stream(stream))
+    return _check(rc, "emoe_measure_scatter_combine", True)
 
 
 def emoe_measure_copy_stream(src, dst, nbytes: int, workgroups: int, stream=None) -> int:

@@ -12,6 +12,8 @@
 //   read stream : a grid-stride read of a buffer with 16-byte loads, eight in flight per lane,
 //                 nothing written: the rate at which HBM delivers a stream that is read once.
 //   copy stream : a plain copy, the kernel of known traffic for scaling hardware-counter readings.
+//   scatter combine : the gate-weighted combine by atomic adds into an fp32 image, what folding the
+//                 combine into the second product costs when a token has several experts.
 #include "common.h"
 
 namespace emoe {
@@ -107,6 +109,37 @@ __global__ __launch_bounds__(256) void copy_stream_kernel(const uintx4* __restri
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// The combine done the way a second product with the combine folded into its epilogue has to do it
+// when a token has several experts: the token's k rows come out of different output tiles at
+// different times, so each is added into an fp32 image of the output with atomics (the image cleared
+// before, converted to the storage type afterwards).  Three kernels: clear, scatter-add one grouped row
+// per wavefront (256 contiguous bytes of atomics per instruction), convert.  Measured against
+// combine_kernel, which reads the k rows of a token and writes the result once.
+__global__ __launch_bounds__(256) void clear_f32_kernel(float4* __restrict__ p, size_t n4) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256)
+        p[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+}
+__global__ __launch_bounds__(256) void scatter_add_kernel(const bf16_t* __restrict__ y_perm, const int32_t* __restrict__ perm,
+                                                          const float* __restrict__ topk_weight, float* __restrict__ image,
+                                                          int A, int d, int k) {
+    const int lane = threadIdx.x & 63;
+    const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
+    for (int r = wave; r < A; r += n_waves) {
+        const int a = perm[r];
+        const float w = topk_weight[a];
+        float* dst = image + (size_t)(a / k) * d;
+        const bf16_t* src = y_perm + (size_t)r * d;
+        for (int c = lane; c < d; c += 64) unsafeAtomicAdd(dst + c, w * bf16_to_f32(src[c]));
+    }
+}
+__global__ __launch_bounds__(256) void convert_f32_kernel(const float4* __restrict__ image, uint2* __restrict__ out, size_t n4) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        const float4 v = image[i];
+        out[i] = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
+                            (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
+    }
+}
+
 }  // namespace
 }  // namespace emoe
 
@@ -151,6 +184,23 @@ int emoe_measure_copy_stream(const void* src, void* dst, size_t bytes, int32_t w
     if (bytes == 0 || bytes % 16 != 0 || workgroups <= 0) return EMOE_ERR_SHAPE;
     copy_stream_kernel<<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const uintx4*>(src),
                                                                                   static_cast<uintx4*>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
+}
+
+int emoe_measure_scatter_combine(const emoe_layer_desc* desc, const void* y_perm, const int32_t* perm,
+                                 const float* topk_weight, float* image, void* out, void* stream) {
+    int rc = validate_desc(desc);
+    if (rc != EMOE_OK) return rc;
+    if (!y_perm || !perm || !topk_weight || !image || !out) return EMOE_ERR_NULL;
+    if (desc->dtype != EMOE_BF16 || desc->d_model % 4 != 0) return EMOE_ERR_UNSUPPORTED;
+    if (desc->T == 0) return EMOE_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t n4 = (size_t)desc->T * desc->d_model / 4;
+    const int A = desc->T * desc->k;
+    clear_f32_kernel<<<2048, 256, 0, st>>>(reinterpret_cast<float4*>(image), n4);
+    scatter_add_kernel<<<2048, 256, 0, st>>>(static_cast<const bf16_t*>(y_perm), perm, topk_weight, image, A, desc->d_model,
+                                             desc->k);
+    convert_f32_kernel<<<2048, 256, 0, st>>>(reinterpret_cast<const float4*>(image), static_cast<uint2*>(out), n4);
     return hipGetLastError() == hipSuccess ? EMOE_OK : EMOE_ERR_DEVICE;
 }
 

@@ -278,6 +278,24 @@ def test_folded_combine_with_several_experts_per_token_is_the_two_calls(gpu_devi
     assert rc == P.EMOE_ERR_NULL        # with k > 1 y_perm is needed
 
 
+@pytest.mark.parametrize("name", ["mid_swiglu_ragged", "mid_topk6", "tiled_swiglu_aligned"])
+def test_combine_by_atomic_scatter_agrees_with_the_combine(gpu_device, name):
+    """The measurement aid that does the combine the way a fold into the second product would (fp32
+    atomics) computes the same output up to the rounding of a differently ordered fp32 sum."""
+    c = [c for c in SMALL_CASES if c.name == name][0]
+    dl = DeviceLayer(gen.make_layer_inputs(c))
+    dl.forward(gather_in_ffn=True)
+    b = dl.buf
+    image = torch.empty((c.T, c.d_model), dtype=torch.float32, device="cuda")
+    out2 = torch.full_like(b.out, float("nan"))
+    P.emoe_measure_scatter_combine(dl.desc, b.y_perm, b.perm, b.topk_weight, image, out2)
+    torch.cuda.synchronize()
+    ref, got = b.out.double(), out2.double()
+    assert torch.isfinite(got).all()
+    # both round one fp32 sum of the same k products to bf16: at most one bf16 step apart
+    assert ((got - ref).abs() <= 2.0 ** -7 * ref.abs() + 1e-6).all()
+
+
 @pytest.mark.parametrize("name", ["mid_swiglu_ragged", "tiled_relu_skewed", "stream_decode", "C1_tiny_f32"])
 def test_layer_forward_in_one_call_equals_the_four_calls(gpu_device, name):
     c = [c for c in SMALL_CASES if c.name == name][0]

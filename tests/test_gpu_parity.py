@@ -293,7 +293,7 @@ def test_combine_by_atomic_scatter_agrees_with_the_combine(gpu_device, name):
     ref, got = b.out.double(), out2.double()
     assert torch.isfinite(got).all()
     # both round one fp32 sum of the same k products to bf16: at most one bf16 step apart
-    assert ((got - ref).abs() <= 2.0 ** -7 * ref.abs() + 1e-6).all()
+    assert ((got - ref).abs() <= 2.0 ** -7 * ref.abs() + 1e-5).all()
 
 
 @pytest.mark.parametrize("name", ["mid_swiglu_ragged", "tiled_relu_skewed", "stream_decode", "C1_tiny_f32"])

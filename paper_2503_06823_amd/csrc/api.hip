@@ -73,9 +73,6 @@ constexpr long long kMidRowsPerSlot = 100;
 constexpr long long kSmallLayerWeightBytes = 320ll << 20;
 constexpr long long kSmallLayerMidFrom = 170, kSmallLayerMidTo = 300;  // rows per slot
 FfnPath ffn_bf16_path(const emoe_layer_desc& d) {
-#ifdef EMOE_X_FORCE_MID
-    return kFfnMid;
-#endif
     const long long A = (long long)d.T * d.k;
     if (A <= kStreamRowsPerSlot * d.S) return kFfnStream;
     if (A <= kMidRowsPerSlot * d.S) return kFfnMid;

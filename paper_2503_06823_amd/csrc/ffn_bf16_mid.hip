@@ -583,9 +583,6 @@ hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets,
     // stream weights, each with as many bytes in flight; and if K is long, in a persistent launch
     // that cuts the tiles along K when even they are clearly fewer than the CUs (with a short K that
     // never pays, and the second kernel's launch is saved).
-#ifdef EMOE_X_OCC2
-    return launch_ktail<EPI, 128, 128, EMOE_X_OCC2, false>(a, gather, offsets, b0, b1, c, partials, A / kTileRows + (S < A ? S : A), S, N, K, st);
-#endif
     constexpr int BNO = EPI == kSwiglu ? 128 : 256;
     // Few rows per slot: token tiles of 64 rows leave LDS for more stages, 96 (80 with 128 weight rows) KiB
     // of weights in flight per CU instead of 64.  (With SwiGLU and 128 weight rows a wavefront of the

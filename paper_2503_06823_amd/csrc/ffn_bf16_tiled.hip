@@ -141,7 +141,6 @@ __device__ __forceinline__ Plan make_plan(int tiles, int k_tiles, int G) {
 // (12 panels for 32 tiles; m fastest over a whole tall slot would need up to 33).
 // rem = number of the tile within the slot -> its m-tile and n-tile.
 constexpr int kBlockM = 8, kBlockN = 4;
-constexpr int kSkipBlocksUpToTiles = 4;  // see the K loop's dispatch
 __device__ __forceinline__ void tile_in_slot(int rem, int m_tiles, int n_tiles, int& mt, int& nt) {
     const int group = rem / (m_tiles * kBlockN);  // group of up to four n-tiles
     const int gn = n_tiles - group * kBlockN < kBlockN ? n_tiles - group * kBlockN : kBlockN;
@@ -310,9 +309,7 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __rest
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float t = acc_read(gate[4 * g + q]);
-#ifndef EMOE_X_NOACT
                     if (EPI == kSwiglu) t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * acc_read(up[4 * g + q]);
-#endif
                     if (EPI == kRelu) t = fmaxf(t, 0.0f);
                     v[q] = t;
                 }
@@ -593,12 +590,11 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 sx = sx1;
             }
         };
-        // Blocks without rows are skipped only in slots of a few tiles, where a tile's padding is a large
-        // share of the slot's matrix work.  In a tall slot the one ragged tile multiplies its padding: the
-        // 32 workgroups of an XCD share operand panels through L2 only while they walk K in step, and a
-        // tile that finishes early falls out of step for good (Mixtral prefill: 20 % more bytes fetched
-        // from beyond L2 when the ragged tiles are cut short).
-        const int my_blocks = slot_tiles > kSkipBlocksUpToTiles ? TB : blocks_of_wavefront(row0, row_end, wm);
+        // Blocks without rows are skipped in every slot: the ragged last tile of a tall slot then finishes
+        // early and walks K out of step with the tiles that share its operand panels through L2, which
+        // fetches more bytes from beyond L2 but costs no time (prefill layer -0.4 %, a layer with slots
+        // of 8 to 1784 rows -4 %).
+        const int my_blocks = blocks_of_wavefront(row0, row_end, wm);
         static_assert(TB == 4, "written out for four token blocks per wavefront");
         // A slot of one m-tile: nobody else reads its weight panel, which is then loaded with the
         // non-temporal hint, so that the stream does not push the token rows out of the caches.
@@ -619,9 +615,6 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         barrier_keep_loads<0>();
 
         if (piece < 0) {
-#ifdef EMOE_X_NOEPI
-            if (K < 0)  // timing experiment: no epilogue at all (K is never negative; uniform)
-#endif
             epilogue<EPI>(acc, c, gather.out_perm, lds, row0, row_end, n0, N, wm, wn, wave, lane);
         } else {  // a K piece of a leftover tile: raw accumulators to the workspace, [register][thread]
             float* dst = partials + kPlanFloats + (size_t)piece * (BM * BR) + tid;

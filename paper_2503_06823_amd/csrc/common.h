@@ -10,6 +10,12 @@ namespace emoe {
 
 constexpr int kWave = 64;
 constexpr int kMaxExperts = 64;
+// The chip the launch shapes are written for: MI355X, 256 compute units in 8 XCDs (workgroup ids are
+// dealt round-robin to the XCDs, each with its own L2).  These numbers shape persistent launches and
+// the tile -> XCD mapping; nothing depends on them for correctness: no kernel waits for another
+// workgroup, so on a device with other numbers the same launches only run slower.
+constexpr int kDeviceCUs = 256;
+constexpr int kDeviceXCDs = 8;
 
 typedef uint16_t bf16_t;  // storage pattern of a bfloat16
 

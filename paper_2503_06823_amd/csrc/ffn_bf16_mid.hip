@@ -67,8 +67,8 @@ constexpr int BK = 64;                     // K elements per tile
 constexpr int ROW_BYTES = BK * 2;          // 128
 constexpr int NW = 4;                      // wavefronts: 2 (tokens) x 2 (weight rows)
 constexpr int TB = 2;                      // 32-token blocks per wavefront
-constexpr int XCDS = 8;
-constexpr int kCUs = 256;
+constexpr int XCDS = kDeviceXCDs;
+constexpr int kCUs = kDeviceCUs;
 constexpr unsigned kRotation = 21;          // K-tile rotation per slot (best of 5, 21, 37 and an even spread)
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
@@ -86,7 +86,7 @@ __device__ __forceinline__ void barrier_keep_loads() {
     asm volatile("" ::: "memory");
 }
 
-constexpr int kGroups = 256;  // the persistent launch: one workgroup per CU
+constexpr int kGroups = kDeviceCUs;  // the persistent launch: one workgroup per CU
 constexpr int kMinShare = 8;     // K tiles per workgroup, at least, when tiles are cut
 constexpr int kMinSpared = 48;   // tiles are cut only if that shortens every workgroup's K walk by this many K tiles
 constexpr long long kRowsPerSlot64 = 48;  // up to that many rows per slot on average: token tiles of 64 rows

@@ -69,8 +69,8 @@ constexpr int TILE_BYTES = BM * ROW_BYTES;  // 32 KiB per operand
 constexpr int SLOTS = 5;                    // LDS ring of operand tiles: x(t), w(t), x(t+1), w(t+1), x(t+2), ...
 constexpr size_t LDS_BYTES = SLOTS * TILE_BYTES;  // 160 KiB, all of a CU's LDS
 static_assert(BK / 16 == 4, "the K loop is written out for four MFMA K-steps per tile");
-constexpr int XCDS = 8;
-constexpr int kPersistentGroups = 256;  // one workgroup per CU
+constexpr int XCDS = kDeviceXCDs;
+constexpr int kPersistentGroups = kDeviceCUs;  // one workgroup per CU
 constexpr int kMaxSplits = 8;           // K pieces per leftover tile, at most
 constexpr int kFixupGroups = 255 * 16;  // workgroups of the fix-up launch: the most units there can be
 constexpr int kPlanFloats = kTiledPlanBytes / 4;  // the plan sits ahead of the partial sums

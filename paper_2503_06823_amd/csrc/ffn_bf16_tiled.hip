@@ -141,6 +141,7 @@ __device__ __forceinline__ Plan make_plan(int tiles, int k_tiles, int G) {
 // (12 panels for 32 tiles; m fastest over a whole tall slot would need up to 33).
 // rem = number of the tile within the slot -> its m-tile and n-tile.
 constexpr int kBlockM = 8, kBlockN = 4;
+constexpr int kSkipBlocksUpToTiles = kBlockM;  // see the K loop's dispatch
 __device__ __forceinline__ void tile_in_slot(int rem, int m_tiles, int n_tiles, int& mt, int& nt) {
     const int group = rem / (m_tiles * kBlockN);  // group of up to four n-tiles
     const int gn = n_tiles - group * kBlockN < kBlockN ? n_tiles - group * kBlockN : kBlockN;
@@ -590,11 +591,14 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                 sx = sx1;
             }
         };
-        // Blocks without rows are skipped in every slot: the ragged last tile of a tall slot then finishes
-        // early and walks K out of step with the tiles that share its operand panels through L2, which
-        // fetches more bytes from beyond L2 but costs no time (prefill layer -0.4 %, a layer with slots
-        // of 8 to 1784 rows -4 %).
-        const int my_blocks = blocks_of_wavefront(row0, row_end, wm);
+        // Blocks without rows are skipped in slots of up to kBlockM tiles (one block of tile_in_slot), where a
+        // tile's padding is a large share of the slot's matrix work.  In a taller slot the one ragged tile
+        // multiplies its padding: the workgroups of an XCD share operand panels through L2 only while they
+        // walk K in step, and a tile that finishes early falls out of step for good.  Measured, bytes fetched
+        // from beyond L2 by the first product / layer time, limit 4 -> 8 -> none: prefill layer 3.15 -> 3.15
+        // -> 5.42 GB, 2.29 -> 2.29 -> 2.34 ms; fine-grained layer 1.31 -> 1.35 -> 1.55 GB, 0.915 -> 0.875
+        // -> 0.869 ms; a layer with slots of 8 to 1784 rows 0.603 -> 0.571 -> 0.575 ms at equal bytes.
+        const int my_blocks = slot_tiles > kSkipBlocksUpToTiles ? TB : blocks_of_wavefront(row0, row_end, wm);
         static_assert(TB == 4, "written out for four token blocks per wavefront");
         // A slot of one m-tile: nobody else reads its weight panel, which is then loaded with the
         // non-temporal hint, so that the stream does not push the token rows out of the caches.

@@ -594,10 +594,11 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
         // Blocks without rows are skipped in slots of up to kBlockM tiles (one block of tile_in_slot), where a
         // tile's padding is a large share of the slot's matrix work.  In a taller slot the one ragged tile
         // multiplies its padding: the workgroups of an XCD share operand panels through L2 only while they
-        // walk K in step, and a tile that finishes early falls out of step for good.  Measured, bytes fetched
-        // from beyond L2 by the first product / layer time, limit 4 -> 8 -> none: prefill layer 3.15 -> 3.15
-        // -> 5.42 GB, 2.29 -> 2.29 -> 2.34 ms; fine-grained layer 1.31 -> 1.35 -> 1.55 GB, 0.915 -> 0.875
-        // -> 0.869 ms; a layer with slots of 8 to 1784 rows 0.603 -> 0.571 -> 0.575 ms at equal bytes.
+        // walk K in step, and a tile that finishes early falls out of step for good.  Skipping everywhere
+        // fetches 5.4 instead of 3.15 GB from beyond L2 in the prefill layer's first product (Mixtral-8x22B
+        // shape: 10.5 instead of 6.6 GB) and gains nothing: with the three policies (limit 4, 8, none) run
+        // in turns inside one process, layer times differ by less than 1 % on every workload (prefill
+        // 2.298 / 2.288 / 2.307 ms, fine-grained layer 0.845 / 0.842 / 0.836 ms).
         const int my_blocks = slot_tiles > kSkipBlocksUpToTiles ? TB : blocks_of_wavefront(row0, row_end, wm);
         static_assert(TB == 4, "written out for four token blocks per wavefront");
         // A slot of one m-tile: nobody else reads its weight panel, which is then loaded with the

@@ -76,7 +76,9 @@ def cmd_kernel_stats(a):
             f.write("\n" + a.note + "\n")
         if a.bench_json:
             b = json.loads(open(a.bench_json).read().strip().splitlines()[-1])
-            keep = {k: b[k] for k in ("value", "ms_per_step", "roofline", "prefill_breakdown_ms", "ceilings") if k in b}
+            keep = {k: b[k] for k in ("value", "ms_per_step", "ms_per_step_eager", "launch", "roofline", "prefill_breakdown_ms",
+                                      "breakdown_ms", "ceilings", "combine_fold_measurement", "layer_tflops",
+                                      "layer_mfma_frac", "layer_weight_gbs", "layer_hbm_frac", "miss_rate") if k in b}
             for sub in ("decode", "c5", "c2"):
                 if sub in b:
                     keep[sub] = {k: b[sub][k] for k in ("value", "ms_per_step", "roofline", "breakdown_ms") if k in b[sub]}
@@ -130,6 +132,15 @@ def cmd_traffic(a):
     print(a.out)
 
 
+def read_durations(directory: str):
+    """{short kernel name: [dispatch duration in ns]} from the kernel_trace.csv of the same run."""
+    dur = collections.defaultdict(list)
+    with open(_find(directory, "kernel_trace.csv"), newline="") as f:
+        for r in csv.DictReader(f):
+            dur[short_name(r["Kernel_Name"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    return dur
+
+
 def cmd_counters(a):
     want = [s for s in (a.kernels or "").split(",") if s]
     table = collections.defaultdict(dict)     # kernel -> counter -> (mean, n)
@@ -138,15 +149,28 @@ def cmd_counters(a):
             if want and not any(w in k for w in want):
                 continue
             table[k][c] = (sum(v) / len(v), len(v))
+        for k, v in read_durations(d).items():
+            if k in table:
+                table[k]["duration_us (dispatch timestamps, counters on)"] = (sum(v) / len(v) / 1e3, len(v))
+    for k, t in table.items():                # derived figures of the matrix-core counter set
+        if "SQ_BUSY_CU_CYCLES" in t and "SQ_VALU_MFMA_BUSY_CYCLES" in t:
+            busy, mfma = t["SQ_BUSY_CU_CYCLES"][0], t["SQ_VALU_MFMA_BUSY_CYCLES"][0]
+            t["matrix pipe busy = MFMA_BUSY / (4 SIMDs x BUSY_CU)"] = (mfma / (4 * busy), 0)
+            dur = t.get("duration_us (dispatch timestamps, counters on)")
+            if dur:
+                t["sustained GHz = BUSY_CU / 256 CUs / duration"] = (busy / a.cus / (dur[0] * 1e3), 0)
+        if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in t:
+            t["TFLOP executed = MOPS_BF16 x 512"] = (t["SQ_INSTS_VALU_MFMA_MOPS_BF16"][0] * 512 / 1e12, 0)
     counters = sorted({c for t in table.values() for c in t})
     with open(a.out, "w") as f:
         f.write(f"# {a.title or 'Hardware counters per dispatch (rocprofv3 --pmc)'}\n\n")
         f.write("Commands (one counter group per run, on the MI355X box from the repository root), then\n"
                 "`python -m paper_2503_06823_amd.profile_tools counters <out dirs> ...` wrote this file:\n\n```\n" + a.command + "\n```\n\n")
-        f.write("Average per dispatch:\n\n| kernel | dispatches | " + " | ".join(counters) + " |\n|---|---|" + "---|" * len(counters) + "\n")
-        for k, t in sorted(table.items(), key=lambda kv: -max(m for m, _ in kv[1].values())):
-            n = max(n for _, n in t.values())
-            f.write(f"| `{k}` | {n} | " + " | ".join(f"{t[c][0]:,.4g}" if c in t else "" for c in counters) + " |\n")
+        kernels = sorted(table, key=lambda k: -max(m for m, _ in table[k].values()))
+        f.write("Average per dispatch (counters are sums over the chip):\n\n| counter | " + " | ".join(f"`{k}`" for k in kernels) + " |\n|---|" + "---|" * len(kernels) + "\n")
+        f.write("| dispatches | " + " | ".join(str(max(n for _, n in table[k].values())) for k in kernels) + " |\n")
+        for c in counters:
+            f.write(f"| {c} | " + " | ".join(f"{table[k][c][0]:,.4g}" if c in table[k] else "" for k in kernels) + " |\n")
         if a.note:
             f.write("\n" + a.note + "\n")
     print(a.out)
@@ -167,6 +191,7 @@ def main(argv=None):
     p.add_argument("--min-bytes", type=float, default=16e6)
     p.set_defaults(fn=cmd_traffic)
     p = sub.add_parser("counters"); p.add_argument("dirs", nargs="+"); common(p); p.add_argument("--kernels", default="")
+    p.add_argument("--cus", type=int, default=256, help="compute units the per-chip cycle counters are divided by")
     p.set_defaults(fn=cmd_counters)
     a = ap.parse_args(argv)
     a.fn(a)

@@ -64,6 +64,10 @@ SMALL_CASES = [
     cfg("stream_k_equals_R", T=9, d_model=128, d_ff=192, E=6, k=3, R=3, index=50),
     # few tokens, few experts, long rows: the bf16 route that puts one workgroup on each token (d_model with a K tail)
     cfg("decode_long_rows", T=40, d_model=2056, d_ff=192, E=12, k=2, R=7, S=9, index=59),
+    # many experts per token: top-8 of 12 resident (streaming and tiles), top-16 with every slot taken
+    cfg("top8_of_12", T=40, d_model=128, d_ff=192, E=16, k=8, R=12, index=83),
+    cfg("top8_of_12_tiles", T=300, d_model=200, d_ff=264, E=16, k=8, R=12, S=14, index=84),
+    cfg("top16_all_slots", act="relu", T=150, d_model=128, d_ff=136, E=32, k=16, R=16, zipf_s=1.1, index=85),
     cfg("single_token", T=1, d_model=128, d_ff=256, E=8, k=2, R=4, index=51),
     cfg("single_expert_dense", T=300, d_model=128, d_ff=256, E=1, k=1, R=1, index=52),
 ]

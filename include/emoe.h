@@ -332,6 +332,8 @@ int emoe_plan_load(int32_t E, int32_t S, int32_t k, const int32_t *expert_of_slo
  *                 the layer's pending load, if any (no stale weights).
  *   layer_end     call after layer i's forward: marks on compute_stream the
  *                 point after which the layer's slots may be overwritten.
+ *   layer_ready   does not block: *ready = 1 if every load enqueued for layer i so
+ *                 far has finished on the GPU (a forward of it would not wait), else 0.
  *   residents     copies layer i's host mirror expert_of_slot [S].
  *   synchronize   blocks the host until every enqueued load has finished.
  *   destroy       synchronizes the side stream, then frees the object.
@@ -352,6 +354,7 @@ int emoe_loader_next_prompt(emoe_loader *loader, int64_t *prompt_index, int32_t 
 int emoe_loader_update(emoe_loader *loader, const int32_t *const *selected, const int32_t *L);
 int emoe_loader_layer_begin(emoe_loader *loader, int32_t layer, void *compute_stream);
 int emoe_loader_layer_end(emoe_loader *loader, int32_t layer, void *compute_stream);
+int emoe_loader_layer_ready(const emoe_loader *loader, int32_t layer, int32_t *ready);
 int emoe_loader_residents(const emoe_loader *loader, int32_t layer, int32_t *expert_of_slot_host);
 int emoe_loader_synchronize(emoe_loader *loader);
 

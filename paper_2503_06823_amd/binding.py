@@ -28,7 +28,7 @@ EXPORTS = ("emoe_status_string", "emoe_workspace_bytes", "emoe_route", "emoe_rou
            "emoe_layer_forward", "emoe_load_experts", "emoe_expected_tokens",
            "emoe_select_experts", "emoe_plan_load", "emoe_prompt_action", "emoe_loader_create", "emoe_loader_destroy",
            "emoe_loader_next_prompt", "emoe_loader_update", "emoe_loader_layer_begin", "emoe_loader_layer_end",
-           "emoe_loader_residents", "emoe_loader_synchronize", "emoe_expected_latency", "emoe_schedule",
+           "emoe_loader_layer_ready", "emoe_loader_residents", "emoe_loader_synchronize", "emoe_expected_latency", "emoe_schedule",
            "emoe_generation_tick", "emoe_measure_mfma_loop", "emoe_measure_read_stream",
            "emoe_measure_copy_stream", "emoe_measure_scatter_combine")
 
@@ -385,6 +385,12 @@ class Loader:
 
     def layer_end(self, layer: int, stream=None) -> int:
         return _check(lib().emoe_loader_layer_end(self._h, int(layer), _stream(stream)), "emoe_loader_layer_end", True)
+
+    def layer_ready(self, layer: int) -> bool:
+        """True if every load enqueued for the layer so far has finished on the GPU (does not block)."""
+        ready = ctypes.c_int32(0)
+        _check(lib().emoe_loader_layer_ready(self._h, int(layer), ctypes.byref(ready)), "emoe_loader_layer_ready", True)
+        return bool(ready.value)
 
     def residents(self, layer: int):
         out = (ctypes.c_int32 * self._slots[layer])()

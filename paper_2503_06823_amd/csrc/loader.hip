@@ -169,6 +169,15 @@ int emoe_loader_layer_end(emoe_loader* ld, int32_t layer, void* compute_stream) 
     return EMOE_OK;
 }
 
+int emoe_loader_layer_ready(const emoe_loader* ld, int32_t layer, int32_t* ready) {
+    if (!ld || !ready) return EMOE_ERR_NULL;
+    if (layer < 0 || layer >= (int)ld->layers.size()) return EMOE_ERR_SHAPE;
+    const hipError_t e = hipEventQuery(ld->layers[layer].loaded);  // never recorded counts as complete
+    if (e != hipSuccess && e != hipErrorNotReady) return EMOE_ERR_DEVICE;
+    *ready = e == hipSuccess ? 1 : 0;
+    return EMOE_OK;
+}
+
 int emoe_loader_residents(const emoe_loader* ld, int32_t layer, int32_t* expert_of_slot_host) {
     if (!ld || !expert_of_slot_host) return EMOE_ERR_NULL;
     if (layer < 0 || layer >= (int)ld->layers.size()) return EMOE_ERR_SHAPE;

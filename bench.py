@@ -588,15 +588,20 @@ def main():
         del inp
         # the small workloads whole, best of three (decode step and Switch-style layer)
         others = {}
-        for key, cfg in (("c4_decode", gen.C4), ("c2_switch", gen.C2)):
+        all_threads = oracle.num_threads()
+        for key, cfg, threads in (("c4_decode", gen.C4, all_threads), ("c2_switch", gen.C2, all_threads),
+                                  ("c2_switch_one_thread", gen.C2, 1), ("c1_tiny", gen.C1, all_threads),
+                                  ("c1_tiny_one_thread", gen.C1, 1)):
             cin = gen.make_layer_inputs(cfg)
+            oracle.set_num_threads(threads)
             ts = []
-            for _ in range(3):
+            for _ in range(3 if threads > 1 else 1):      # one thread takes seconds: a single run
                 t = time.perf_counter()
                 oracle.layer_forward(cin)
                 ts.append(time.perf_counter() - t)
-            others[key] = {"value": cfg.T / min(ts), "unit": "tokens/s", "best_of": 3, "seconds": sorted(ts),
-                           "sample": f"all {cfg.T} tokens"}
+            others[key] = {"value": cfg.T / min(ts), "unit": "tokens/s", "threads": threads, "best_of": len(ts),
+                           "seconds": sorted(ts), "sample": f"all {cfg.T} tokens"}
+        oracle.set_num_threads(all_threads)
         result["cpu_baseline"]["other_workloads"] = others
         log(f"cpu baseline, small workloads whole: {others}")
 

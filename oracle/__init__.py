@@ -55,7 +55,7 @@ def _c():
         _lib = ctypes.CDLL(build_oracle())
         for name in ("oracle_gate_logits", "oracle_route_mask_then_topk", "oracle_route_rank_then_skip",
                      "oracle_route_unrestricted", "oracle_permute", "oracle_gather_rows",
-                     "oracle_expert_ffn_rows", "oracle_combine_tokens", "oracle_num_threads"):
+                     "oracle_expert_ffn_rows", "oracle_combine_tokens", "oracle_num_threads", "oracle_set_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -74,6 +74,11 @@ def _check(rc: int, where: str):
 
 def num_threads() -> int:
     return int(_c().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads for the loops over independent rows (for timing the oracle as a baseline; results do not depend on it)."""
+    _c().oracle_set_num_threads(int(n))
 
 
 def _i32(a) -> np.ndarray:

@@ -243,6 +243,17 @@ int oracle_combine_tokens(int n_tokens, const int32_t *tokens, int k, int d, con
     return ORACLE_OK;
 }
 
+/* Number of threads for the loops over independent rows (timing of the oracle as a baseline only:
+ * the results do not depend on it). */
+int oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+    return ORACLE_OK;
+}
+
 int oracle_num_threads(void) {
     int n = 1;
 #ifdef _OPENMP

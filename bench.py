@@ -424,7 +424,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards by tokens with no "
-              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "exchange). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -4,12 +4,43 @@
 
 #include "common.h"
 
+#include <mutex>
+
 namespace emoe {
 
 namespace {
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+constexpr int kMaxDevices = 64;
+std::mutex shape_mutex;
+DeviceShape shape_of_device[kMaxDevices] = {};
 size_t elem_bytes(const emoe_layer_desc& d) { return d.dtype == EMOE_F32 ? 4 : 2; }
 }  // namespace
+
+hipError_t device_shape(DeviceShape* out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(shape_mutex);
+    DeviceShape& s = shape_of_device[dev];
+    if (s.cus == 0) {
+        int cus = 0, xcds = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess || xcds < 1) xcds = 1;
+        if (cus < 1) return hipErrorInvalidDevice;
+        if (cus % xcds != 0) xcds = 1;  // ids then map to themselves
+        int groups = cus < kMaxGroups ? cus : kMaxGroups;
+        groups -= groups % xcds;
+        if (groups < xcds) { xcds = 1; groups = cus < kMaxGroups ? cus : kMaxGroups; }
+        s.xcds = xcds;
+        s.groups = groups;
+        s.cus = cus;
+    }
+    *out = s;
+    return hipSuccess;
+}
 
 int validate_desc(const emoe_layer_desc* d) {
     if (d == nullptr) return EMOE_ERR_NULL;

@@ -10,12 +10,19 @@ namespace emoe {
 
 constexpr int kWave = 64;
 constexpr int kMaxExperts = 64;
-// The chip the launch shapes are written for: MI355X, 256 compute units in 8 XCDs (workgroup ids are
-// dealt round-robin to the XCDs, each with its own L2).  These numbers shape persistent launches and
-// the tile -> XCD mapping; nothing depends on them for correctness: no kernel waits for another
-// workgroup, so on a device with other numbers the same launches only run slower.
-constexpr int kDeviceCUs = 256;
-constexpr int kDeviceXCDs = 8;
+// The chip the kernels are written for is MI355X: 256 compute units in 8 XCDs (workgroup ids are
+// dealt round-robin to the XCDs, each with its own L2).  The launch shapes take both numbers from
+// the device at run time (device_shape()); nothing depends on them for correctness: no kernel waits
+// for another workgroup.  kMaxGroups bounds the persistent launches, whose partial-sum workspaces
+// are sized for that many workgroups.
+constexpr int kMaxGroups = 256;
+struct DeviceShape {
+    int cus;     // compute units
+    int xcds;    // XCDs the workgroup ids are dealt to, round-robin
+    int groups;  // workgroups of a persistent launch: one per CU, at most kMaxGroups, a multiple of xcds
+};
+// Shape of the current device, queried once per device.
+hipError_t device_shape(DeviceShape* out);
 
 typedef uint16_t bf16_t;  // storage pattern of a bfloat16
 

@@ -67,8 +67,6 @@ constexpr int BK = 64;                     // K elements per tile
 constexpr int ROW_BYTES = BK * 2;          // 128
 constexpr int NW = 4;                      // wavefronts: 2 (tokens) x 2 (weight rows)
 constexpr int TB = 2;                      // 32-token blocks per wavefront
-constexpr int XCDS = kDeviceXCDs;
-constexpr int kCUs = kDeviceCUs;
 constexpr unsigned kRotation = 21;          // K-tile rotation per slot (best of 5, 21, 37 and an even spread)
 
 enum Epilogue { kPlain = 0, kSwiglu = 1, kRelu = 2 };
@@ -86,7 +84,7 @@ __device__ __forceinline__ void barrier_keep_loads() {
     asm volatile("" ::: "memory");
 }
 
-constexpr int kGroups = kDeviceCUs;  // the persistent launch: one workgroup per CU
+constexpr int kGroups = kMaxGroups;  // the persistent launch has one workgroup per CU, at most this many
 constexpr int kMinShare = 8;     // K tiles per workgroup, at least, when tiles are cut
 constexpr int kMinSpared = 48;   // tiles are cut only if that shortens every workgroup's K walk by this many K tiles
 constexpr long long kRowsPerSlot64 = 48;  // up to that many rows per slot on average: token tiles of 64 rows
@@ -160,7 +158,7 @@ __global__ __launch_bounds__(64 * NW) void mid_gemm_bf16(const bf16_t* __restric
                                                      const int32_t* __restrict__ offsets,
                                                      const bf16_t* __restrict__ b0, const bf16_t* __restrict__ b1,
                                                      bf16_t* __restrict__ c, float* __restrict__ partials, int S, int N,
-                                                     int K, int n_tiles) {
+                                                     int K, int n_tiles, int XCDS) {
     constexpr int W_TILE = BR * ROW_BYTES;             // 32 or 16 KiB
     constexpr int X_TILE = BM * ROW_BYTES;             // 16 or 8 KiB
     constexpr int STAGE_BYTES = X_TILE + W_TILE;
@@ -554,13 +552,18 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
         attr_set.store(true, std::memory_order_release);
     }
     const int n_tiles = (N + BNO - 1) / BNO;
+    DeviceShape shape;
+    hipError_t es = device_shape(&shape);
+    if (es != hipSuccess) return es;
     if (PERSIST) {
-        kern<<<kGroups, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
-        mid_fixup<EPI, BM, BR><<<kGroups - 1, 64 * NW, 0, st>>>(offsets, c, gather.out_perm, partials, S, N, K, n_tiles, kGroups);
+        kern<<<shape.groups, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles, shape.xcds);
+        if (shape.groups > 1)
+            mid_fixup<EPI, BM, BR><<<shape.groups - 1, 64 * NW, 0, st>>>(offsets, c, gather.out_perm, partials, S, N, K, n_tiles,
+                                                                        shape.groups);
     } else {
         const long long tiles = m_tiles * n_tiles;
-        const unsigned blocks = (unsigned)((tiles + XCDS - 1) / XCDS * XCDS);
-        kern<<<blocks, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
+        const unsigned blocks = (unsigned)((tiles + shape.xcds - 1) / shape.xcds * shape.xcds);
+        kern<<<blocks, 64 * NW, kLds, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles, shape.xcds);
     }
     return hipGetLastError();
 }
@@ -576,6 +579,10 @@ hipError_t launch_ktail(const bf16_t* a, RowGather gather, const int32_t* offset
 template <int EPI>
 hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets, const bf16_t* b0, const bf16_t* b1,
                       bf16_t* c, float* partials, long long A, int S, int N, int K, hipStream_t st) {
+    DeviceShape shape;
+    hipError_t es = device_shape(&shape);
+    if (es != hipSuccess) return es;
+    const int kCUs = shape.cus;
     // every slot adds at most one partial m-tile to the A / 128 whole ones
     const long long m_tiles = A / kTileRows + (S < A ? S : A);
     // Tiles of 256 weight rows, unless they would leave CUs without a tile (the second product of a

@@ -250,7 +250,10 @@ hipError_t launch_one(const bf16_t* a, RowGather gather, const int32_t* offsets,
                       int N, int K, hipStream_t st) {
     if constexpr (EPI != kSwiglu) {
         // fewer 64-row units than workgroup slots (2 per CU): halve the unit so the whole chip streams
-        if ((long long)S * ((N + 63) / 64) < 2 * 256) return launch_wr<EPI, 32>(a, gather, offsets, b0, b1, c, S, N, K, st);
+        DeviceShape shape;
+        hipError_t es = device_shape(&shape);
+        if (es != hipSuccess) return es;
+        if ((long long)S * ((N + 63) / 64) < 2 * shape.cus) return launch_wr<EPI, 32>(a, gather, offsets, b0, b1, c, S, N, K, st);
     }
     return launch_wr<EPI, 64>(a, gather, offsets, b0, b1, c, S, N, K, st);
 }

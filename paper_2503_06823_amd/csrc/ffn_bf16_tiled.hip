@@ -69,10 +69,8 @@ constexpr int TILE_BYTES = BM * ROW_BYTES;  // 32 KiB per operand
 constexpr int SLOTS = 5;                    // LDS ring of operand tiles: x(t), w(t), x(t+1), w(t+1), x(t+2), ...
 constexpr size_t LDS_BYTES = SLOTS * TILE_BYTES;  // 160 KiB, all of a CU's LDS
 static_assert(BK / 16 == 4, "the K loop is written out for four MFMA K-steps per tile");
-constexpr int XCDS = kDeviceXCDs;
-constexpr int kPersistentGroups = kDeviceCUs;  // one workgroup per CU
 constexpr int kMaxSplits = 8;           // K pieces per leftover tile, at most
-constexpr int kFixupGroups = 255 * 16;  // workgroups of the fix-up launch: the most units there can be
+constexpr int kFixupGroups = (kMaxGroups - 1) * 16;  // workgroups of the fix-up launch: the most units there can be
 constexpr int kPlanFloats = kTiledPlanBytes / 4;  // the plan sits ahead of the partial sums
 constexpr unsigned kRotation = 21;  // K-tile rotation per slot
 constexpr int NW = 4;            // wavefronts per workgroup, arranged 2 (tokens) x NW/2 (weight rows)
@@ -345,7 +343,7 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
                                                          const bf16_t* __restrict__ b0,
                                                          const bf16_t* __restrict__ b1, bf16_t* __restrict__ c,
                                                          float* __restrict__ partials, int S, int N, int K,
-                                                         int n_tiles) {
+                                                         int n_tiles, int XCDS) {
     constexpr int BNO = EPI == kSwiglu ? BR / 2 : BR;  // output columns per tile
     extern __shared__ __align__(16) char lds[];
 
@@ -692,9 +690,13 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
     }
-    kern<<<kPersistentGroups, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles);
+    DeviceShape shape;
+    hipError_t es = device_shape(&shape);
+    if (es != hipSuccess) return es;
+    // persistent: one workgroup per CU (the partial sums of the tiles cut along K are sized for kMaxGroups)
+    kern<<<shape.groups, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles, shape.xcds);
     splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, gather.out_perm, reinterpret_cast<const int*>(partials),
-                                                        partials + kPlanFloats, S, N, K, n_tiles, kPersistentGroups);
+                                                        partials + kPlanFloats, S, N, K, n_tiles, shape.groups);
     return hipGetLastError();
 }
 

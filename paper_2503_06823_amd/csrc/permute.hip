@@ -1,8 +1,9 @@
 // Stable counting sort of the A = T*k assignments by slot id and the row gather into slot-contiguous
 // order.  The per-slot row counts are the per-expert "workload" of eMoE Section 3.2.2.
 //
-// Four launches (two when all assignments fit one workgroup: count, scan and place fused), no
-// atomics on global memory, so the result is the unique stable permutation:
+// Four launches (three up to 65 536 assignments: scan and place fused; two when all assignments fit
+// one workgroup: count, scan and place fused), no atomics on global memory, so the result is the
+// unique stable permutation:
 //   1. count    : each workgroup histograms its chunk of kPermuteChunk assignments (LDS counters)
 //   2. scan     : per slot, exclusive prefix over the workgroups; then prefix over the slots
 //   3. place    : each workgroup ranks its assignments in order with wave ballots and writes
@@ -221,6 +222,83 @@ __global__ __launch_bounds__(kSmallThreads) void sort_small_kernel(const int32_t
     }
 }
 
+// scan + place in one launch, for up to kScanPlaceBlocks chunks (65 536 assignments): every workgroup adds
+// up the chunk counts of the count kernel itself - all of them for the slots' offsets, those of the
+// chunks before its own for its first row in each slot - instead of waiting for a scan launch; with
+// few chunks those are a few thousand cached integers.  One thread per assignment as in
+// sort_small_kernel.  Workgroup 0 also writes slot_counts and slot_offsets.
+constexpr int kScanPlaceBlocks = 64;
+__global__ __launch_bounds__(kSmallThreads) void scan_place_kernel(const int32_t* __restrict__ topk_expert,
+                                                                   const int32_t* __restrict__ slot_of_expert,
+                                                                   const int32_t* __restrict__ block_counts, int n_blocks,
+                                                                   int32_t* __restrict__ slot_counts,
+                                                                   int32_t* __restrict__ slot_offsets,
+                                                                   int32_t* __restrict__ perm,
+                                                                   int32_t* __restrict__ inv_perm, int A, int E, int S) {
+    __shared__ int wave_cnt[kSmallWaves][kMaxExperts];  // [wavefront][slot]: count, then the first row of that wavefront's share
+    __shared__ int part_total[kSmallWaves][kMaxExperts], part_before[kSmallWaves][kMaxExperts];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int a = blockIdx.x * kSmallThreads + threadIdx.x;
+    const int key = key_of(topk_expert, slot_of_expert, a, A, E, S);
+    // wavefront w adds up chunks w, w + 16, ... for slot `lane`
+    int total = 0, before = 0;
+    if (lane < S) {
+        for (int b = wave; b < n_blocks; b += kSmallWaves) {
+            const int c = block_counts[(size_t)b * S + lane];
+            total += c;
+            if (b < (int)blockIdx.x) before += c;
+        }
+    }
+    part_total[wave][lane] = total;
+    part_before[wave][lane] = before;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int rank = 0, mine = 0;  // lane s ends up with this wavefront's count for slot s
+    for (int s = 0; s < S; ++s) {
+        const unsigned long long m = __ballot(key == s);
+        if (key == s) rank = __popcll(m & below);
+        if (lane == s) mine = __popcll(m);
+    }
+    wave_cnt[wave][lane] = mine;
+    __syncthreads();
+    if (wave == 0) {  // lane = slot
+        int c = 0, b4 = 0;
+#pragma unroll
+        for (int w = 0; w < kSmallWaves; ++w) {
+            c += part_total[w][lane];
+            b4 += part_before[w][lane];
+        }
+        int incl = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        if (blockIdx.x == 0) {
+            if (lane < S) {
+                slot_counts[lane] = c;
+                slot_offsets[lane] = incl - c;
+            }
+            if (lane == S - 1) slot_offsets[S] = incl;
+        }
+        int run = incl - c + b4;
+#pragma unroll
+        for (int w = 0; w < kSmallWaves; ++w) {
+            const int n = wave_cnt[w][lane];
+            wave_cnt[w][lane] = run;
+            run += n;
+        }
+    }
+    __syncthreads();
+    if (key >= 0) {
+        const int r = wave_cnt[wave][key] + rank;
+        perm[r] = a;
+        inv_perm[a] = r;
+    } else if (a < A) {
+        inv_perm[a] = -1;
+    }
+}
+
 // One wavefront per grouped row: x_perm[r,:] = x[perm[r]/k,:].  Rows past the number of placed
 // assignments (only when some were left out) are not written.
 template <int kElemBytes>
@@ -250,6 +328,10 @@ hipError_t launch_permute(const emoe_layer_desc& d, const void* x, const int32_t
     if (n_blocks == 1) {
         sort_small_kernel<<<1, kSmallThreads, 0, st>>>(topk_expert, slot_of_expert, counts, offsets, perm, inv_perm, A, d.E,
                                                   d.S);
+    } else if (n_blocks <= kScanPlaceBlocks) {
+        count_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, A, d.E, d.S);
+        scan_place_kernel<<<n_blocks, kSmallThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, n_blocks, counts,
+                                                              offsets, perm, inv_perm, A, d.E, d.S);
     } else {
         count_kernel<<<n_blocks, kThreads, 0, st>>>(topk_expert, slot_of_expert, block_counts, A, d.E, d.S);
         scan_kernel<<<1, 1024, 0, st>>>(block_counts, n_blocks, d.S, counts, offsets);

@@ -68,6 +68,8 @@ SMALL_CASES = [
     cfg("top8_of_12", T=40, d_model=128, d_ff=192, E=16, k=8, R=12, index=83),
     cfg("top8_of_12_tiles", T=300, d_model=200, d_ff=264, E=16, k=8, R=12, S=14, index=84),
     cfg("top16_all_slots", act="relu", T=150, d_model=128, d_ff=136, E=32, k=16, R=16, zipf_s=1.1, index=85),
+    # more than 65 536 assignments: the permutation's three-launch path (scan as a launch of its own)
+    cfg("permute_many_chunks", T=35000, d_model=64, d_ff=72, E=16, k=2, R=5, zipf_s=1.1, index=86),
     cfg("single_token", T=1, d_model=128, d_ff=256, E=8, k=2, R=4, index=51),
     cfg("single_expert_dense", T=300, d_model=128, d_ff=256, E=1, k=1, R=1, index=52),
 ]

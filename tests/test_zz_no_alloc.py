@@ -49,7 +49,8 @@ def _both(c, with_rows):
 
 
 def test_static_scratch_permute_equals_the_workspace_one(gpu_device):
-    for c, with_rows in ((_case("static_large", 300, T=9000, E=64, k=6, R=24, S=40), True),     # 53 workgroups x 40 slots
+    for c, with_rows in ((_case("static_largest", 304, T=40000, E=32, k=2, R=11, S=16, d_model=16), False),  # 79 x 16: three launches
+                         (_case("static_large", 300, T=9000, E=64, k=6, R=24, S=40), True),     # 53 workgroups x 40 slots
                          (_case("static_smaller", 301, T=2500, E=16, k=2, R=7, S=9), False),    # 5 workgroups x 9 slots
                          (_case("static_one_workgroup", 302, T=300, E=8, k=2, R=4, S=4), True)):
         plain, static = _both(c, with_rows)

@@ -175,28 +175,6 @@ __device__ __forceinline__ int blocks_of_wavefront(int row0, int row_end, int wm
     return ((row_end - row0 + 31) / 32 - wm + 1) / 2;
 }
 
-// tile number -> slot, first row and end of the tile's rows, n-tile
-__device__ __forceinline__ void decode_tile(const int32_t* __restrict__ offsets, int S, int n_tiles, int L, int& slot,
-                                            int& row0, int& row_end, int& nt) {
-    int rem = L;
-    slot = 0; row0 = 0; row_end = 0; nt = 0;
-    for (int s = 0; s < S; ++s) {
-        const int b = offsets[s], e = offsets[s + 1];
-        const int tiles = (e - b + BM - 1) / BM;
-        const int span = tiles * n_tiles;
-        if (rem < span) {
-            slot = s;
-            int mt;
-            tile_in_slot(rem, tiles, n_tiles, mt, nt);
-            const int rpt = rows_per_tile(e - b, tiles);
-            row0 = b + mt * rpt;
-            row_end = row0 + rpt < e ? row0 + rpt : e;
-            return;
-        }
-        rem -= span;
-    }
-}
-
 // One 32 x 32 output block of a wavefront: token block mi, output-column block ni.  `gate` holds the
 // accumulators (for SwiGLU the gate rows), `up` the matching up rows (unused otherwise).
 // A lane holds token lane%32 and weight rows 8g + 4*(lane/32) + 0..3.
@@ -655,8 +633,11 @@ __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restric
     if (u >= plan.left * UNITS) return;
     const int tile = u / UNITS, unit = u % UNITS;
     const int mi = unit / NB, ni = unit % NB;
-    int slot, row0, row_end, nt;
-    decode_tile(offsets, S, n_tiles, plan.rounds * G + tile, slot, row0, row_end, nt);
+    int slot, row0, row_end, nt, slot_tiles;
+    // the slot table in registers, as in the main kernel: a walk over slot_offsets in memory is a chain of up to S
+    // dependent loads, longer than everything else this kernel does
+    const SlotTable table = make_slot_table(offsets, S, n_tiles, lane);
+    decode_tile(table, S, n_tiles, lane, plan.rounds * G + tile, slot, row0, row_end, nt, slot_tiles);
     if (row0 + tile_block(wave / WN, mi) * 32 >= row_end) return;  // this wavefront's block holds no rows: nothing was written
     floatx16 gate, up;
 #pragma unroll

@@ -111,7 +111,7 @@ def test_layers_load_one_after_the_other(gpu_device):
     """Watched from the host with the loader's non-blocking query, so that no second stream's place in a
     hardware queue can blur the picture: layer i becomes ready a whole copy time after layer i - 1."""
     import time
-    n_layers = 3
+    n_layers = 6
     desc = P.make_desc(64, D, F, E, K, S, "bf16", "swiglu")
     h1, h3, h2 = pinned_experts(E, 3)
     layers = []
@@ -132,6 +132,7 @@ def test_layers_load_one_after_the_other(gpu_device):
 
     t0 = time.perf_counter()
     loader.update([[0, 1]] * n_layers)                    # every layer changes both experts
+    watched_from = (time.perf_counter() - t0) * 1e3       # enqueueing takes the host a few ms: the first loads may be done by now
     at = [None] * n_layers
     while any(a is None for a in at) and time.perf_counter() - t0 < 5.0:
         for i in range(n_layers):
@@ -140,9 +141,13 @@ def test_layers_load_one_after_the_other(gpu_device):
     loader.synchronize()
     loader.close()
     assert all(a is not None for a in at), "a load did not finish within 5 s"
-    # layer 0 is usable long before the whole chain is done (loads that ran side by side would all end near the end)
-    assert at[0] < 0.5 * at[-1], f"layer 0 was ready after {at[0]:.2f} ms of {at[-1]:.2f} ms for all {n_layers} layers"
-    # and the loads do not overlap: each finishes a whole copy time after the one before
-    for i in range(1, n_layers):
+    assert at == sorted(at), f"layers became ready out of order: {at}"
+    # Loads that ran side by side would share the link and all end near the end.  Every load that ended while
+    # the host was watching must end a whole copy time after the one before it.
+    seen = [i for i in range(1, n_layers) if at[i - 1] > watched_from + 0.2]
+    if len(seen) < 2:
+        pytest.skip(f"only {len(seen)} loads ended while the host watched (enqueued in {watched_from:.2f} ms, ready at {at})")
+    for i in seen:
         assert at[i] - at[i - 1] >= 0.8 * floor_ms, (
-            f"layer {i}'s load finished {at[i] - at[i - 1]:.2f} ms after layer {i - 1}'s; two experts need at least {floor_ms:.2f} ms")
+            f"layer {i}'s load finished {at[i] - at[i - 1]:.2f} ms after layer {i - 1}'s; two experts need at least {floor_ms:.2f} ms "
+            f"(ready at {at})")

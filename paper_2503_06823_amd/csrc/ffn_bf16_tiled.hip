@@ -291,7 +291,7 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __rest
                     v[q] = t;
                 }
                 // columns wn*(BNO/2) + ni*32 + 8g + 4*(lane/32) .. +3: chunk j, its lower or upper half
-                const int j = wn * (BNO / 16) + ni * 4 + g;
+                const int j = wn * (BNO / WN / 8) + ni * 4 + g;
                 *reinterpret_cast<bf16x4*>(lds + r * ROWB + ((j ^ (r & 15)) * 16) + (lane >> 5) * 8) =
                     __builtin_convertvector(v, bf16x4);
             }
@@ -303,8 +303,8 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[WB][TB], bf16_t* __rest
     const int jc = lane % CPR;
     const int n = n0 + jc * 8;
 #pragma unroll 4
-    for (int it = 0; it < 64 / RPS; ++it) {
-        const int r = wave * 64 + it * RPS + lane / CPR;
+    for (int it = 0; it < BM / NW / RPS; ++it) {
+        const int r = wave * (BM / NW) + it * RPS + lane / CPR;
         const uint4 val = *reinterpret_cast<const uint4*>(lds + r * ROWB + ((jc ^ (r & 15)) * 16));
         if (row0 + r < row_end && n < N) {
             // combine folded in (second product, one expert per token): the row goes to its token's row of the output

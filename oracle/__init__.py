@@ -191,6 +191,7 @@ class LayerResult:
     tokens: np.ndarray                  # tokens for which `out` was computed
     out: Optional[np.ndarray]           # [len(tokens), d] float64
     y_rows: Dict[int, np.ndarray]       # permuted row index -> y row (float64), for the rows computed
+    h_rows: Optional[Dict[int, np.ndarray]] = None   # the same rows of the intermediate h (float64)
 
 
 def layer_forward(inp, tokens: Optional[Sequence[int]] = None, with_ffn: bool = True) -> LayerResult:
@@ -213,7 +214,9 @@ def layer_forward(inp, tokens: Optional[Sequence[int]] = None, with_ffn: bool = 
     rows = pm.inv_perm[a]
     row_token = (pm.perm[rows] // k).astype(np.int32)
     row_slot = np.asarray(inp.slot_of_expert)[idx.reshape(-1)[a]].astype(np.int32)
-    y = expert_ffn_rows(row_token, row_slot, inp.x, inp.w1_slots, inp.w3_slots, inp.w2_slots, cfg.act, cfg.dtype)
+    y, h = expert_ffn_rows(row_token, row_slot, inp.x, inp.w1_slots, inp.w3_slots, inp.w2_slots, cfg.act, cfg.dtype,
+                           return_h=True)
     row_index = np.arange(a.shape[0], dtype=np.int32).reshape(-1, k)
     out = combine_tokens(tok, w, row_index, y)
-    return LayerResult(logits, idx, w, pm, tok, out, {int(r): y[i] for i, r in enumerate(rows)})
+    return LayerResult(logits, idx, w, pm, tok, out, {int(r): y[i] for i, r in enumerate(rows)},
+                       {int(r): h[i] for i, r in enumerate(rows)})

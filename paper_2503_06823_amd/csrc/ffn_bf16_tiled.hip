@@ -616,8 +616,9 @@ __global__ __launch_bounds__(64 * NW) void grouped_gemm_bf16(const bf16_t* __res
 // the chip.  The plan (how many leftover tiles, how many pieces)
 // is read from the head of the workspace, where the main kernel left it: when nothing was split,
 // which the host cannot know, every workgroup exits after one load.
+constexpr int kFixupUnitsPerGroup = 4;  // units per workgroup of the fix-up launch, one per 64 * NW threads
 template <int EPI>
-__global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
+__global__ __launch_bounds__(64 * NW * kFixupUnitsPerGroup) void splitk_fixup(const int32_t* __restrict__ offsets, bf16_t* __restrict__ c,
                                                         const int32_t* __restrict__ out_perm,
                                                         const int* __restrict__ hdr,
                                                         const float* __restrict__ partials, int S, int N, int K,
@@ -628,8 +629,10 @@ __global__ __launch_bounds__(64 * NW) void splitk_fixup(const int32_t* __restric
     Plan plan;  // uniform address: scalar loads
     plan.tiles = hdr[0]; plan.rounds = hdr[1]; plan.left = hdr[2]; plan.splits = hdr[3];
     if (plan.splits <= 1) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int u = blockIdx.x;  // the launch covers the most units there can be
+    // a workgroup holds kFixupUnitsPerGroup independent units (there is no barrier in this kernel): when nothing was
+    // cut, which is the common case, a quarter as many workgroups have to start only to find that out
+    const int tid = threadIdx.x % (64 * NW), lane = tid & 63, wave = tid >> 6;
+    const int u = blockIdx.x * kFixupUnitsPerGroup + threadIdx.x / (64 * NW);  // the launch covers the most units there can be
     if (u >= plan.left * UNITS) return;
     const int tile = u / UNITS, unit = u % UNITS;
     const int mi = unit / NB, ni = unit % NB;
@@ -676,7 +679,7 @@ hipError_t launch_cfg(const bf16_t* a, RowGather gather, const int32_t* offsets,
     if (es != hipSuccess) return es;
     // persistent: one workgroup per CU (the partial sums of the tiles cut along K are sized for kMaxGroups)
     kern<<<shape.groups, 64 * NW, LDS_BYTES, st>>>(a, gather, offsets, b0, b1, c, partials, S, N, K, n_tiles, shape.xcds);
-    splitk_fixup<EPI><<<kFixupGroups, 64 * NW, 0, st>>>(offsets, c, gather.out_perm, reinterpret_cast<const int*>(partials),
+    splitk_fixup<EPI><<<kFixupGroups / kFixupUnitsPerGroup, 64 * NW * kFixupUnitsPerGroup, 0, st>>>(offsets, c, gather.out_perm, reinterpret_cast<const int*>(partials),
                                                         partials + kPlanFloats, S, N, K, n_tiles, shape.groups);
     return hipGetLastError();
 }

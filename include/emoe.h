@@ -14,8 +14,11 @@
  *
  * Conventions for every entry point
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
- *     addresses; the caller owns every buffer; the library allocates nothing,
- *     frees nothing and keeps no state between calls.
+ *     addresses; the caller owns every buffer; the library allocates no device
+ *     memory, frees nothing and keeps no state between calls, with three
+ *     exceptions that the calls concerned describe: the emoe_loader object, the
+ *     fixed array behind emoe_permute_static, and the number of compute units
+ *     and XCDs of each device, which are looked up once and remembered.
  *   - Tensors are dense row-major.  Element type is desc->dtype: fp32, or
  *     bf16 stored as 16-bit patterns.  Pointers must be 16-byte aligned.
  *   - `stream` is a hipStream_t (NULL = the null stream).  Calls only enqueue

@@ -135,6 +135,14 @@ def test_zero_tokens_is_a_noop(gpu_device):
     assert P.emoe_expert_ffn(d, buf.x_perm, buf.slot_offsets, dummy, dummy, dummy, buf.y_perm, buf.ffn_ws,
                              buf.ffn_ws.numel()) == P.EMOE_OK
     assert P.emoe_combine(d, buf.y_perm, buf.inv_perm, buf.topk_weight, buf.out) == P.EMOE_OK
+    assert P.emoe_expert_ffn_gather_combine(d, dummy, buf.perm, buf.inv_perm, buf.slot_offsets, dummy, dummy, dummy,
+                                            buf.topk_weight, buf.y_perm, buf.out, buf.ffn_ws, buf.ffn_ws.numel()) == P.EMOE_OK
+    torch.cuda.synchronize()
+    assert not buf.slot_counts.cpu().numpy().any() and not buf.slot_offsets.cpu().numpy().any()
+    buf.slot_counts.fill_(7)
+    buf.slot_offsets.fill_(7)
+    assert P.emoe_permute_static(d, dummy, buf.topk_expert, soe, buf.slot_counts, buf.slot_offsets, buf.perm, buf.inv_perm,
+                                 buf.x_perm) == P.EMOE_OK
     torch.cuda.synchronize()
     assert not buf.slot_counts.cpu().numpy().any() and not buf.slot_offsets.cpu().numpy().any()
 

@@ -70,6 +70,10 @@ SMALL_CASES = [
     cfg("top16_all_slots", act="relu", T=150, d_model=128, d_ff=136, E=32, k=16, R=16, zipf_s=1.1, index=85),
     # more than 65 536 assignments: the permutation's three-launch path (scan as a launch of its own)
     cfg("permute_many_chunks", T=35000, d_model=64, d_ff=72, E=16, k=2, R=5, zipf_s=1.1, index=86),
+    # expert counts that fill no group of 8, 16 or 32 gate rows
+    cfg("experts_5", T=130, d_model=136, d_ff=200, E=5, k=2, R=3, S=4, index=87),
+    cfg("experts_24", act="relu", T=260, d_model=200, d_ff=264, E=24, k=3, R=11, S=20, zipf_s=1.1, index=88),
+    cfg("experts_48_decode", T=48, d_model=2056, d_ff=136, E=48, k=4, R=30, S=40, index=89),
     cfg("single_token", T=1, d_model=128, d_ff=256, E=8, k=2, R=4, index=51),
     cfg("single_expert_dense", T=300, d_model=128, d_ff=256, E=1, k=1, R=1, index=52),
 ]

@@ -10,11 +10,19 @@ namespace emoe {
 namespace {
 
 template <typename T> struct Pack;
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 template <> struct Pack<bf16_t> {
     static constexpr int N = 8;
+    template <bool ONCE>
     __device__ static void load(const bf16_t* p, float (&v)[8]) {
-        uint4 r = *reinterpret_cast<const uint4*>(p);
-        uint32_t w[4] = {r.x, r.y, r.z, r.w};
+        uint32_t w[4];
+        if (ONCE) {  // rows that will not be read again soon and do not fit the caches anyway: non-temporal
+            const uintx4 r = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(p));
+            w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+        } else {
+            const uint4 r = *reinterpret_cast<const uint4*>(p);
+            w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             v[2 * i] = __uint_as_float(w[i] << 16);
@@ -30,6 +38,7 @@ template <> struct Pack<bf16_t> {
 };
 template <> struct Pack<float> {
     static constexpr int N = 4;
+    template <bool ONCE>
     __device__ static void load(const float* p, float (&v)[4]) {
         float4 r = *reinterpret_cast<const float4*>(p);
         v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
@@ -39,7 +48,7 @@ template <> struct Pack<float> {
     }
 };
 
-template <typename T>
+template <typename T, bool ONCE>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_perm, const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ topk_weight, T* __restrict__ out,
                                                       int T_, int d, int k, int chunks) {
@@ -74,7 +83,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
                 w[jj] = ok ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), j)) : 0.0f;
 #pragma unroll
                 for (int i = 0; i < N; ++i) v[jj][i] = 0.0f;
-                if (ok && c < d) Pack<T>::load(y_perm + (size_t)r * d + c, v[jj]);
+                if (ok && c < d) Pack<T>::template load<ONCE>(y_perm + (size_t)r * d + c, v[jj]);
             }
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
@@ -96,8 +105,16 @@ hipError_t launch_t(const emoe_layer_desc& d, const void* y_perm, const int32_t*
     long long units = (long long)d.T * chunks;
     long long blocks = (units + 3) / 4;
     if (blocks > 256 * 32) blocks = 256 * 32;
-    combine_kernel<T><<<(int)blocks, 256, 0, st>>>(static_cast<const T*>(y_perm), inv_perm, w, static_cast<T*>(out),
-                                                   d.T, d.d_model, d.k, chunks);
+    // y_perm larger than half the 256 MB Infinity Cache: its rows come from HBM whatever is done, and without the
+    // non-temporal hint they push each other through the caches (fine-grained layer, 201 MB: 47 -> 44 us); a smaller
+    // one is still cached from the second product that wrote it (prefill layer, 67 MB: 22.6 us, 23.8 with the hint)
+    const bool once = (size_t)d.T * d.k * d.d_model * sizeof(T) > ((size_t)128 << 20);
+    if (once)
+        combine_kernel<T, true><<<(int)blocks, 256, 0, st>>>(static_cast<const T*>(y_perm), inv_perm, w, static_cast<T*>(out),
+                                                             d.T, d.d_model, d.k, chunks);
+    else
+        combine_kernel<T, false><<<(int)blocks, 256, 0, st>>>(static_cast<const T*>(y_perm), inv_perm, w, static_cast<T*>(out),
+                                                              d.T, d.d_model, d.k, chunks);
     return hipGetLastError();
 }
 
